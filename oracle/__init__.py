@@ -1,0 +1,179 @@
+"""ctypes view of the fp64 CPU oracle (oracle/arith_oracle.c).
+
+TEST INFRASTRUCTURE: only tests/, the smoke check and the benchmark's
+cpu_baseline leg may import this package.  It knows nothing about the HIP
+library and the HIP library knows nothing about it; both are fed the same
+arrays by the caller.
+
+Each wrapper below only marshals NumPy arrays; the arithmetic is in the C file,
+which cites the passages of the paper it follows.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16, F64 = 0, 1, 2
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.ao_lattice.argtypes = [C.c_int32, C.c_double, C.c_void_p]
+        L.ao_lattice.restype = None
+        L.ao_lattice_paper.argtypes = [C.c_int32, C.c_double, C.c_void_p]
+        L.ao_lattice_paper.restype = None
+        L.ao_step_rows.argtypes = [
+            C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int32, C.c_void_p,
+            C.c_void_p, C.c_double, C.c_int32, C.c_double, C.c_void_p,
+            C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        L.ao_step_rows.restype = C.c_int
+        L.ao_bigram_logits.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_double,
+            C.c_int32, C.c_int, C.c_void_p]
+        L.ao_bigram_logits.restype = None
+        L.ao_decode.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_double,
+            C.c_int, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+            C.c_double, C.c_int32, C.c_double, C.c_int32, C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        L.ao_decode.restype = C.c_int
+        L.ao_encode.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_double,
+            C.c_int, C.c_int32, C.c_void_p, C.c_int32, C.c_double, C.c_int32,
+            C.c_double, C.c_int32, C.c_void_p, C.c_void_p]
+        L.ao_encode.restype = C.c_int
+        L.ao_max_threads.argtypes = []
+        L.ao_max_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _stored(a):
+    """(contiguous array, dtype code) for a stored tensor.
+
+    float32 -> F32, float64 -> F64, uint16 -> BF16 (raw bfloat16 bit patterns).
+    """
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32:
+        return a, F32
+    if a.dtype == np.float64:
+        return a, F64
+    if a.dtype == np.uint16:
+        return a, BF16
+    raise TypeError("stored tensors must be float32, float64 or uint16 (bf16 bits)")
+
+
+def max_threads():
+    return int(lib().ao_max_threads())
+
+
+def lattice(N, u):
+    out = np.empty(N, dtype=np.float64)
+    lib().ao_lattice(N, float(u), _ptr(out))
+    return out
+
+
+def lattice_paper(N, b):
+    out = np.empty(N, dtype=np.float64)
+    lib().ao_lattice_paper(N, float(b), _ptr(out))
+    return out
+
+
+def step(logits, codes, temp=1.0, top_k=0, top_p=1.0, finished=None,
+         eos_id=-1, row_ids=None, V=None, nthreads=1):
+    """One decode step for every row.  Returns a dict of per-row arrays."""
+    logits, dt = _stored(logits)
+    if logits.ndim == 1:
+        logits = logits[None, :]
+    ld = logits.shape[1]
+    V = ld if V is None else int(V)
+    codes = np.ascontiguousarray(codes, dtype=np.float64)
+    rows = codes.shape[0]
+    rid = None if row_ids is None else np.ascontiguousarray(row_ids, dtype=np.int64)
+    fin = None if finished is None else np.ascontiguousarray(finished, dtype=np.uint8)
+    out = dict(
+        token=np.empty(rows, np.int32), c_next=np.empty(rows, np.float64),
+        p=np.empty(rows, np.float64), f_lo=np.empty(rows, np.float64),
+        f_hi=np.empty(rows, np.float64), delta=np.empty(rows, np.float64),
+        nuc_margin=np.empty(rows, np.float64), n_kept=np.empty(rows, np.int32),
+        finished=np.empty(rows, np.uint8))
+    rc = lib().ao_step_rows(
+        _ptr(logits), dt, rows, ld, V, _ptr(rid), _ptr(codes), float(temp),
+        int(top_k), float(top_p), _ptr(fin), int(eos_id), _ptr(out["token"]),
+        _ptr(out["c_next"]), _ptr(out["p"]), _ptr(out["f_lo"]),
+        _ptr(out["f_hi"]), _ptr(out["delta"]), _ptr(out["nuc_margin"]),
+        _ptr(out["n_kept"]), _ptr(out["finished"]), int(nthreads))
+    if rc != 0:
+        raise MemoryError("oracle step failed")
+    return out
+
+
+def bigram_logits(E, U, prev, scale=3.0, round_mode=0):
+    E, dt = _stored(E)
+    U, dt2 = _stored(U)
+    assert dt == dt2
+    V, d = E.shape
+    assert U.shape == (d, V)
+    x = np.empty(V, dtype=np.float64)
+    lib().ao_bigram_logits(_ptr(E), _ptr(U), dt, V, d, float(scale), int(prev),
+                           int(round_mode), _ptr(x))
+    return x
+
+
+def decode(E, U, prompts, N, T, codes0, temp=1.0, top_k=0, top_p=1.0,
+           eos_id=-1, scale=3.0, round_mode=0, nthreads=1, records=False):
+    E, dt = _stored(E)
+    U, dt2 = _stored(U)
+    assert dt == dt2
+    V, d = E.shape
+    prompts = np.ascontiguousarray(prompts, dtype=np.int32)
+    B = prompts.shape[0]
+    codes0 = np.ascontiguousarray(codes0, dtype=np.float64).reshape(-1)
+    assert codes0.shape[0] == B * N
+    tokens = np.empty((B * N, T), dtype=np.int32)
+    cf = np.empty(B * N, dtype=np.float64)
+    p = np.empty((B * N, T), dtype=np.float64) if records else None
+    dl = np.empty((B * N, T), dtype=np.float64) if records else None
+    rc = lib().ao_decode(_ptr(E), _ptr(U), dt, V, d, float(scale),
+                         int(round_mode), _ptr(prompts), B, int(N), int(T),
+                         _ptr(codes0), float(temp), int(top_k), float(top_p),
+                         int(eos_id), _ptr(tokens), _ptr(cf), _ptr(p), _ptr(dl),
+                         int(nthreads))
+    if rc != 0:
+        raise MemoryError("oracle decode failed")
+    out = dict(tokens=tokens.reshape(B, N, T), codes_final=cf.reshape(B, N))
+    if records:
+        out["p"] = p.reshape(B, N, T)
+        out["delta"] = dl.reshape(B, N, T)
+    return out
+
+
+def encode(E, U, prompt, seq, temp=1.0, top_k=0, top_p=1.0, eos_id=-1,
+           scale=3.0, round_mode=0):
+    """Interval (w, P) of a sequence or prefix: codes in [w, w+P) decode to it."""
+    E, dt = _stored(E)
+    U, dt2 = _stored(U)
+    assert dt == dt2
+    V, d = E.shape
+    seq = np.ascontiguousarray(seq, dtype=np.int32)
+    w = C.c_double()
+    P = C.c_double()
+    rc = lib().ao_encode(_ptr(E), _ptr(U), dt, V, d, float(scale),
+                         int(round_mode), int(prompt), _ptr(seq), seq.shape[0],
+                         float(temp), int(top_k), float(top_p), int(eos_id),
+                         C.byref(w), C.byref(P))
+    if rc != 0:
+        raise MemoryError("oracle encode failed")
+    return w.value, P.value
