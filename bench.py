@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the arithmetic-sampling decode path on one MI355X.
+
+One "step" is one whole as_decode call of the headline configuration
+(V=32128, d=512, bf16, B=16 prompts x N=64 codes = 1024 rows, T=64 decode steps,
+temperature 0.7, EOS sticky): lattice init, then per decode step the logits
+GEMM and the fused sampling kernel.  Inputs (weights, prompts, shifts) are
+synthetic, seeded and already resident in HBM when timing starts.
+
+Prints ONE JSON line: whole-job code-steps/s, plus
+  roofline      the fused sampling kernel (the dominant HBM-bound kernel): its
+                algorithmic bytes per launch over its average launch duration,
+                taken from the dispatch's own HIP events during the timed region
+  roofline_cold the same kernel launched alone over >1 GiB of rotating logits
+                buffers, so no row can be served from the 256 MB Infinity Cache
+  logits_gemm   the MFMA logits kernel: achieved TFLOP/s against the bf16 peak
+  cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on a bounded
+                sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold (rotating buffers) kernel leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (codes are independent, so more GPUs would each "
+              "run this same path on their share of the codes); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2210_15458_amd import binding as B
+    from paper_2210_15458_amd import synth
+
+    cfg = synth.CONFIGS[args.config]
+    V, d, Bn, N, T = cfg["V"], cfg["d"], cfg["B"], cfg["N"], cfg["T"]
+    temp, top_k, top_p, eos = cfg["temp"], cfg["top_k"], cfg["top_p"], cfg["eos_id"]
+    R = Bn * N
+    tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+
+    def up(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    E, U = synth.bigram_weights(V, d, seed=0, dtype=cfg["dtype"])
+    Ed, Ud = up(E), up(U)
+    model = B.Model(Ed, Ud, scale=cfg["scale"])
+    del Ud
+    prompts = up(synth.prompts(Bn, V, seed=1))
+    u = up(synth.shifts(Bn, seed=2))
+    ctx = B.Ctx(R, V, tdt)
+    tokens = torch.empty((Bn, N, T), dtype=torch.int32, device="cuda")
+
+    def decode():
+        B.as_decode(ctx, model, prompts, N, T, u, temp, top_k, top_p, eos, tokens)
+
+    for _ in range(args.warmup):
+        decode()
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        decode()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    step_ms, step_n, step_drop = ctx.profile_read(0)
+    gemm_ms, gemm_n, _ = ctx.profile_read(1)
+    thr_ms, thr_n, _ = ctx.profile_read(2)
+    ctx.profile(False)
+
+    # same region once more without per-dispatch events, to show what they cost
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        decode()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+
+    wall = t1 - t0
+    code_steps = R * T * args.steps
+    # rows that were still running, per launch: finished rows are not read
+    tk = tokens.cpu().numpy().reshape(R, T)
+    active = np.ones((R, T), dtype=bool)
+    for t in range(1, T):
+        active[:, t] = active[:, t - 1] & (tk[:, t - 1] != eos)
+    active_rows_per_launch = float(active.sum()) / T
+    bytes_per_row = V * esz + 18           # the logits row + code in/out, token, flags
+    step_avg_us = step_ms / max(step_n, 1) * 1e3
+    achieved = active_rows_per_launch * bytes_per_row / (step_avg_us * 1e-6) / 1e9 if step_n else None
+
+    out = {
+        "metric": "code-steps/sec and sampling-kernel HBM GB/s (% peak), V=32128, N*B=1024",
+        "value": code_steps / wall,
+        "unit": "code-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg['name']}: as_decode V={V} d={d} {cfg['dtype']} "
+                               f"weights+logits, B={Bn} N={N} (R={R}) T={T} temp={temp} top_k={top_k} "
+                               f"top_p={top_p} eos={eos}; one step = one whole decode ({R * T} code-steps)",
+                   "storage": cfg["dtype"], "rows": R, "decode_steps": T,
+                   "value_without_dispatch_events": code_steps / (t3 - t2)},
+        "roofline": {
+            "kernel": "step_kernel (fused sampling step), as launched inside as_decode",
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
+            "avg_launch_us": step_avg_us, "launches": step_n, "untimed_launches": step_drop,
+            "bytes_per_code_step": bytes_per_row, "active_rows_per_launch": active_rows_per_launch,
+            "note": "rows follow the logits GEMM that just wrote them, so part of each row can come from "
+                    "the Infinity Cache rather than HBM; see roofline_cold for the HBM-only figure"},
+        "logits_gemm": {
+            "bound": "mfma", "avg_launch_us": gemm_ms / max(gemm_n, 1) * 1e3, "launches": gemm_n,
+            "achieved": (2.0 * R * d * V / (gemm_ms / max(gemm_n, 1) * 1e-3) / 1e12) if gemm_n else None,
+            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"},
+    }
+    if out["logits_gemm"]["achieved"]:
+        out["logits_gemm"]["frac"] = out["logits_gemm"]["achieved"] / MFMA_BF16_PEAK_TFLOPS
+    if thr_n:
+        out["threshold_kernel"] = {"avg_launch_us": thr_ms / thr_n * 1e3, "launches": thr_n}
+
+    # ---- cold leg: the sampling kernel alone, rotating over > 1 GiB of logits
+    if not args.no_cold:
+        ld = (V + 7) // 8 * 8
+        nbuf = max(2, int(np.ceil((1.25 * 2 ** 30) / (R * ld * esz))))
+        bufs = torch.empty((nbuf, R, ld), dtype=tdt, device="cuda")
+        prev = prompts.repeat_interleave(N).contiguous()
+        for i in range(nbuf):
+            # distinct, realistic rows in every buffer: logits of a shifted token set
+            B.as_bigram_logits(ctx, model, ((prev + 977 * i) % V).to(torch.int32).contiguous(), bufs[i])
+        codes = up(synth.uniform_codes(R, seed=4))
+        tok = torch.empty(R, dtype=torch.int32, device="cuda")
+        cout = torch.empty(R, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        reps = 8
+        for i in range(nbuf):                       # warm-up pass (code, not data: buffers keep rotating)
+            B.as_step(ctx, bufs[i], codes, temp, top_k, top_p, tok, cout)
+        torch.cuda.synchronize()
+        ctx.profile_read(0)
+        ctx.profile(True)
+        for _ in range(reps):
+            for i in range(nbuf):
+                B.as_step(ctx, bufs[i], codes, temp, top_k, top_p, tok, cout)
+        ms, n, _ = ctx.profile_read(0)
+        ctx.profile(False)
+        us = ms / n * 1e3
+        ach = R * bytes_per_row / (us * 1e-6) / 1e9
+        out["roofline_cold"] = {
+            "kernel": "step_kernel alone, rotating over %d logits buffers (%.2f GiB)" % (
+                nbuf, nbuf * R * ld * esz / 2 ** 30),
+            "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "avg_launch_us": us, "launches": n, "code_steps_per_s": R / (us * 1e-6)}
+        del bufs
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported, not a target)
+    if not args.no_cpu:
+        import oracle
+        nthreads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+        ld = (V + 7) // 8 * 8
+        prev = prompts.repeat_interleave(N).contiguous()
+        logits = torch.empty((R, ld), dtype=tdt, device="cuda")
+        B.as_bigram_logits(ctx, model, prev, logits)
+        torch.cuda.synchronize()
+        stored = logits.view(torch.int16).cpu().numpy().view(np.uint16) if tdt == torch.bfloat16 else logits.cpu().numpy()
+        codes = synth.uniform_codes(R, seed=4).astype(np.float64)
+        sample_rows = R
+        oracle.step(stored[:64], codes[:64], temp=temp, top_k=top_k, top_p=top_p, V=V, nthreads=nthreads)  # warm
+        c0 = time.perf_counter()
+        reps = 0
+        while True:
+            oracle.step(stored[:sample_rows], codes[:sample_rows], temp=temp, top_k=top_k, top_p=top_p, V=V,
+                        nthreads=nthreads)
+            reps += 1
+            if time.perf_counter() - c0 > 1.5 or reps >= 16:
+                break
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {
+            "value": sample_rows * reps / (c1 - c0), "unit": "code-steps/s", "cores": nthreads, "kind": "oracle",
+            "sample": f"oracle step (fp64) over the {sample_rows} rows of the first decode step's logits, "
+                      f"{reps} repetitions, {nthreads} OpenMP threads, {c1 - c0:.2f} s wall; sampling step "
+                      f"only (the oracle's fp64 logits GEMM is not included)"}
+
+    print(json.dumps(out))
+    ctx.close()
+    model.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,205 @@
+/*
+ * arith_sampling.h -- C ABI of the MI355X (gfx950) arithmetic-sampling library.
+ *
+ * The library runs the data-parallel decode path of arithmetic sampling
+ * (Vilnis et al., "Arithmetic Sampling: Parallel Diverse Decoding for Large
+ * Language Models", arXiv 2210.15458): every sequence is driven by one code
+ * point c in [0,1); at each step the code selects the token whose interval of
+ * the vocabulary-order cumulative distribution holds it and is then rescaled
+ * to that interval (Sec. 4.1, Algorithm 1).  N codes of one prompt sit on a
+ * randomly shifted lattice (Sec. 4.2, Definition "Arithmetic sampling").
+ * Codes never interact (Remark after Prop. 1), so all calls below are batched
+ * over independent rows.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE point to memory of the GPU that was current when
+ *     the context was created; the caller owns them and keeps them alive until
+ *     the stream has run past the call.  The library never copies them to the
+ *     host and never frees them.
+ *   - Calls are asynchronous: work is enqueued on the context's HIP stream and
+ *     the function returns.  No call synchronises the device.
+ *   - Argument errors are detected on the host before anything is launched and
+ *     reported through the return code; as_last_error() gives a message.
+ *     Nothing throws, aborts or prints.
+ *   - Data errors (NaN logits, a code outside [0,1)) are not detected; the
+ *     result for such a row is unspecified but memory safe: the emitted token
+ *     lies in [0,V) and the new code in [0, 1 - 2^-24].
+ *   - A logit of -inf is legal and means probability zero.
+ *   - as_step / as_step_ex allocate nothing and touch only the context's
+ *     fixed workspace.  as_decode and as_bigram_logits (re)allocate the
+ *     context's decode workspace when a call needs more than any earlier one.
+ *   - One context must not be used from two host threads at once.
+ */
+#ifndef ARITH_SAMPLING_H
+#define ARITH_SAMPLING_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct as_ctx as_ctx;
+typedef struct as_model as_model;
+
+typedef enum {
+    AS_OK = 0,
+    AS_ERR_INVALID_ARG = 1, /* null pointer, size out of range, bad parameter  */
+    AS_ERR_UNSUPPORTED = 2, /* valid request this build cannot serve           */
+    AS_ERR_ALLOC = 3,       /* device or host allocation failed                */
+    AS_ERR_DEVICE = 4       /* HIP reported an error (launch, stream, ...)     */
+} as_status;
+
+/* storage type of logits and of model weights */
+typedef enum { AS_F32 = 0, AS_BF16 = 1 } as_dtype;
+
+/* ---------------------------------------------------------------- context */
+
+/*
+ * Create a context bound to the current HIP device.
+ *   max_rows      largest number of rows (codes) a single call will carry, >= 1
+ *   V             vocabulary size, 1 <= V <= AS_MAX_VOCAB
+ *   logits_dtype  storage type of every logits tensor passed with this context
+ *   hip_stream    a hipStream_t (as void*) all work is enqueued on; NULL = the
+ *                 default stream.  The stream must outlive the context.
+ * On success *out owns a small device workspace; release it with
+ * as_ctx_destroy (which synchronises the stream first).
+ */
+as_status as_ctx_create(as_ctx **out, int64_t max_rows, int32_t V,
+                        as_dtype logits_dtype, void *hip_stream);
+as_status as_ctx_destroy(as_ctx *ctx);
+
+/* Message for the last failing call made with this context (or, with NULL, for
+ * the last failing call of this thread that had no context).  The string is
+ * owned by the library and valid until the next failing call. */
+const char *as_last_error(const as_ctx *ctx);
+
+#define AS_MAX_VOCAB (1 << 21)
+
+/*
+ * Measurement aid (not part of the method): with profiling on, every launch of
+ * the sampling kernel, the logits kernel and the threshold kernel carries its
+ * own start/stop HIP events, taken from the dispatch on the context's stream.
+ * as_ctx_profile_read synchronises the stream, returns the summed kernel time
+ * and the number of timed launches since the last read for
+ *   kernel 0: fused sampling step   1: logits (bigram) kernel   2: threshold
+ * and resets the counters.  At most 16384 launches per kernel are timed between
+ * reads; further ones run untimed and are counted in *untimed.  Any output
+ * pointer may be NULL.  Switching profiling on makes the first launches create
+ * events (a host-side allocation).
+ */
+as_status as_ctx_profile(as_ctx *ctx, int enable);
+as_status as_ctx_profile_read(as_ctx *ctx, int kernel, double *total_ms,
+                              int64_t *launches, int64_t *untimed);
+
+/* ------------------------------------------------------------ single step */
+
+/*
+ * One step of Algorithm 1 (Sec. 4.1) for `rows` independent codes.
+ *
+ * For row r: x_v = logits[r, v] / temp; optional top-k and nucleus masks (the
+ * logit modifiers of Sec. 2; masked tokens get probability zero, Sec. 5 top-k
+ * paragraph); softmax over the kept tokens; inclusive cumulative sums F in
+ * VOCABULARY ORDER (the total order of Sec. 3.1); token = the first v with
+ * F(v) > c, i.e. c lies in [F(v-1), F(v)); c' = (c - F(v-1)) / (F(v) -
+ * F(v-1)).  Arithmetic is fp32 per element with fp64 carries.
+ *
+ *   logits      DEVICE [rows, ld] row-major, ctx dtype, ld >= V; columns
+ *               V..ld-1 are never read.  Rows whose start is 16-byte aligned
+ *               take the vector path; others a slower element path.
+ *   codes       DEVICE float[rows], each in [0,1)
+ *   temp        > 0
+ *   top_k       keep the k highest logits and everything tied with the k-th;
+ *               <= 0 or >= V: off
+ *   top_p       keep the smallest set of highest-probability value groups whose
+ *               mass (after top-k) reaches top_p, whole groups; <= 0 or >= 1: off
+ *   tokens_out  DEVICE int32[rows]
+ *   codes_out   DEVICE float[rows]; may be the same pointer as codes
+ */
+as_status as_step(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
+                  const float *codes, float temp, int32_t top_k, float top_p,
+                  int32_t *tokens_out, float *codes_out);
+
+/*
+ * as_step with the per-row state of a running decode (Algorithm 1's stopping
+ * rule in its padded fixed-length form, Sec. 3.3) and optional records.
+ *
+ *   finished_in   DEVICE uint8[rows] or NULL.  A row with a non-zero flag emits
+ *                 eos_id, keeps its code, and its logits are not read.
+ *   eos_id        token that ends a sequence; < 0: none
+ *   finished_out  DEVICE uint8[rows] or NULL; 1 if the row was finished on
+ *                 entry or emitted eos_id now.  May alias finished_in.
+ *   prob_out      DEVICE float[rows] or NULL: probability of the emitted token
+ *   flo_out       DEVICE float[rows] or NULL: F(v-1), start of its interval
+ *   row_ids       DEVICE int32[rows] or NULL: logits row read by each code
+ *                 (several codes may share a row), each in [0, logits_rows)
+ *   logits_rows   number of rows in `logits` when row_ids is given
+ */
+as_status as_step_ex(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
+                     const float *codes, float temp, int32_t top_k, float top_p,
+                     int32_t *tokens_out, float *codes_out,
+                     const uint8_t *finished_in, int32_t eos_id,
+                     uint8_t *finished_out, float *prob_out, float *flo_out,
+                     const int32_t *row_ids, int64_t logits_rows);
+
+/* ---------------------------------------------------------------- lattice */
+
+/*
+ * Codes of Sec. 4.2 on the circular lattice with spacing 1/N:
+ * codes_out[b*N + i] = (i + u[b]) / N for i = 0..N-1, evaluated in fp64 and
+ * rounded once to fp32 (then kept <= 1 - 2^-24).
+ *   u          DEVICE float[B], each in [0,1): one shared shift per prompt
+ *   codes_out  DEVICE float[B*N];  B*N <= ctx max_rows
+ */
+as_status as_lattice(as_ctx *ctx, const float *u, int32_t B, int32_t N,
+                     float *codes_out);
+
+/* ------------------------------------------- synthetic sequence model + decode */
+
+/*
+ * Low-rank bigram model standing in for P(X_t | X_<t) of Sec. 3.3:
+ * logits[v] = (scale / sqrt(d)) * sum_k E[prev, k] * U[k, v].
+ *   E       DEVICE [V, d] row-major, wdtype; borrowed, must outlive the model
+ *   U       DEVICE [d, V] row-major, wdtype; read once here (the model keeps
+ *           its own K-contiguous copy) and not needed afterwards
+ *   d       rank, >= 1.  AS_BF16 weights with d a multiple of 64 and a 16-byte
+ *           aligned E run on the MFMA kernel; anything else on a plain
+ *           dot-product kernel meant for small models only
+ * The call enqueues a re-layout kernel on the default stream and waits for it.
+ */
+as_status as_model_create_bigram(as_model **out, const void *E, const void *U,
+                                 int32_t V, int32_t d, float scale,
+                                 as_dtype wdtype);
+as_status as_model_destroy(as_model *model);
+
+/*
+ * logits_out[r, :] = model logits given prev[r], for r < rows (AS_BF16 weights
+ * use bf16 MFMA with fp32 accumulation; the result is rounded once to the ctx
+ * logits dtype).
+ *   prev        DEVICE int32[rows], each in [0,V)
+ *   logits_out  DEVICE [rows, ld], ld >= V; columns V..ld-1 are left untouched
+ */
+as_status as_bigram_logits(as_ctx *ctx, const as_model *model,
+                           const int32_t *prev, int64_t rows, void *logits_out,
+                           int64_t ld);
+
+/*
+ * Whole decode (Algorithm 1 for every code of the lattice of Sec. 4.2):
+ * codes from as_lattice, then T times { logits from the model given the
+ * previous token; as_step_ex with EOS kept sticky }.  Exactly the sequence of
+ * the exported calls above, enqueued back to back with no host round trip.
+ *   prompts     DEVICE int32[B]: the token every code of prompt b starts from
+ *   u           DEVICE float[B]
+ *   tokens_out  DEVICE int32[B, N, T]
+ *   codes_out   DEVICE float[B, N] final codes, or NULL
+ * B*N <= ctx max_rows; model V must equal ctx V.
+ */
+as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts,
+                    int32_t B, int32_t N, int32_t T, const float *u, float temp,
+                    int32_t top_k, float top_p, int32_t eos_id,
+                    int32_t *tokens_out, float *codes_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARITH_SAMPLING_H */

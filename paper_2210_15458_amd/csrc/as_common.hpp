@@ -1,0 +1,207 @@
+// Shared declarations of the HIP library: context, model, error plumbing and
+// the wave-level primitives (DPP scans/reductions for 64-wide wavefronts).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/arith_sampling.h"
+
+namespace as {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------- host state
+
+struct DeviceBuf {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+
+// Optional per-kernel timing: when switched on, every launch of a profiled
+// kernel carries its own start/stop events (taken from the dispatch itself,
+// not from separate stream markers), read back by as_ctx_profile_read.
+enum KernelId { kKernelStep = 0, kKernelLogits = 1, kKernelThreshold = 2, kKernelCount = 3 };
+constexpr size_t kProfileCapacity = 16384;      // timed launches per kernel between reads
+
+struct ProfileSlot {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+struct Profile {
+    bool on = false;
+    std::vector<ProfileSlot> slots[kKernelCount];   // created on demand, reused after a read
+    size_t used[kKernelCount] = {0, 0, 0};
+    size_t dropped[kKernelCount] = {0, 0, 0};
+};
+
+}  // namespace as
+
+struct as_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int64_t max_rows = 0;
+    int32_t V = 0;
+    as_dtype dtype = AS_BF16;
+    // fixed workspace (allocated at creation): per-row truncation thresholds
+    float *thr = nullptr;          // [max_rows]
+    // decode workspace (grown on demand by as_decode)
+    as::DeviceBuf logits;          // [rows, ld]
+    as::DeviceBuf state;           // codes f32[rows] | prev i32[rows] | finished u8[rows]
+    as::Profile prof;
+    std::string err;
+};
+
+struct as_model {
+    int device = 0;
+    int32_t V = 0;
+    int32_t d = 0;
+    float scale = 0.f;
+    as_dtype wdtype = AS_BF16;
+    const void *E = nullptr;       // borrowed [V, d]
+    void *Ut = nullptr;            // owned    [V, d]  (U transposed: K contiguous)
+};
+
+namespace as {
+
+as_status fail(as_ctx *ctx, as_status code, const std::string &msg);
+as_status hip_fail(as_ctx *ctx, hipError_t e, const char *what);
+
+#define AS_HIP_TRY(ctx, expr)                                        \
+    do {                                                             \
+        hipError_t _e = (expr);                                      \
+        if (_e != hipSuccess) return ::as::hip_fail((ctx), _e, #expr); \
+    } while (0)
+
+// Launch on the context's stream; with profiling on, attach dispatch events.
+bool profile_acquire(as_ctx *ctx, int kid, hipEvent_t *start, hipEvent_t *stop);
+
+template <class K, class... A>
+inline void launch(as_ctx *ctx, int kid, K kernel, dim3 grid, dim3 block, size_t lds, A... args)
+{
+    hipEvent_t s = nullptr, e = nullptr;
+    if (ctx->prof.on && profile_acquire(ctx, kid, &s, &e))
+        hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, ctx->stream, s, e, 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, (unsigned)lds, ctx->stream, args...);
+}
+
+// -------------------------------------------------------------- launch entry
+// (implemented in as_step.hip / as_model.hip; called only from as_api.hip)
+
+struct StepArgs {
+    const void *logits;
+    int64_t rows;
+    int64_t ld;
+    int32_t V;
+    as_dtype dtype;
+    const float *codes;
+    float temp;
+    const float *thr;            // per-row keep threshold on raw logits, or null
+    int32_t *tokens_out;
+    int64_t tok_stride;          // tokens_out[r * tok_stride]
+    float *codes_out;
+    const uint8_t *finished_in;
+    int32_t eos_id;
+    uint8_t *finished_out;
+    float *prob_out;
+    float *flo_out;
+    const int32_t *row_ids;
+    int32_t *prev_out;           // decode state: next step's conditioning token, or null
+};
+
+as_status launch_step(as_ctx *ctx, const StepArgs &a);
+as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
+                           const uint8_t *finished_in, const int32_t *row_ids,
+                           float temp, int32_t top_k, float top_p, float *thr_out);
+as_status launch_lattice(as_ctx *ctx, const float *u, int32_t B, int32_t N, float *codes_out,
+                         const int32_t *prompts, int32_t *prev_out, uint8_t *finished_out);
+as_status launch_transpose(const void *U, void *Ut, int32_t d, int32_t V, as_dtype wdtype);
+as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *prev,
+                               int64_t rows, void *logits_out, int64_t ld);
+
+// ------------------------------------------------------------ wave primitives
+// Data-parallel-primitive (DPP) cross-lane moves.  bound_ctrl is off, so a lane
+// whose source is outside its row (or that is masked out) receives `old`.
+
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_i32(int old, int src)
+{
+    return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_f32(float old, float src)
+{
+    return __builtin_bit_cast(
+        float, dpp_i32<CTRL, ROW_MASK>(__builtin_bit_cast(int, old), __builtin_bit_cast(int, src)));
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ double dpp_f64(double old, double src)
+{
+    long long o = __builtin_bit_cast(long long, old), s = __builtin_bit_cast(long long, src);
+    int lo = dpp_i32<CTRL, ROW_MASK>((int)o, (int)s);
+    int hi = dpp_i32<CTRL, ROW_MASK>((int)(o >> 32), (int)(s >> 32));
+    long long r = ((long long)hi << 32) | (unsigned int)lo;
+    return __builtin_bit_cast(double, r);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave, lane order.
+__device__ __forceinline__ float wave_scan_add(float x)
+{
+    x += dpp_f32<kRowShr1>(0.f, x);
+    x += dpp_f32<kRowShr2>(0.f, x);
+    x += dpp_f32<kRowShr4>(0.f, x);
+    x += dpp_f32<kRowShr8>(0.f, x);
+    x += dpp_f32<kRowBcast15, 0xa>(0.f, x);
+    x += dpp_f32<kRowBcast31, 0xc>(0.f, x);
+    return x;
+}
+__device__ __forceinline__ double wave_scan_add(double x)
+{
+    x += dpp_f64<kRowShr1>(0.0, x);
+    x += dpp_f64<kRowShr2>(0.0, x);
+    x += dpp_f64<kRowShr4>(0.0, x);
+    x += dpp_f64<kRowShr8>(0.0, x);
+    x += dpp_f64<kRowBcast15, 0xa>(0.0, x);
+    x += dpp_f64<kRowBcast31, 0xc>(0.0, x);
+    return x;
+}
+
+__device__ __forceinline__ float read_lane(float x, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
+__device__ __forceinline__ double read_lane(double x, int lane)
+{
+    long long v = __builtin_bit_cast(long long, x);
+    int lo = __builtin_amdgcn_readlane((int)v, lane);
+    int hi = __builtin_amdgcn_readlane((int)(v >> 32), lane);
+    long long r = ((long long)hi << 32) | (unsigned int)lo;
+    return __builtin_bit_cast(double, r);
+}
+
+// Sum / max over the wave, result in every lane (wave-uniform).
+__device__ __forceinline__ float wave_sum(float x) { return read_lane(wave_scan_add(x), 63); }
+__device__ __forceinline__ double wave_sum(double x) { return read_lane(wave_scan_add(x), 63); }
+
+__device__ __forceinline__ float wave_max(float x)
+{
+    const float ninf = -__builtin_inff();
+    x = fmaxf(x, dpp_f32<kRowShr1>(ninf, x));
+    x = fmaxf(x, dpp_f32<kRowShr2>(ninf, x));
+    x = fmaxf(x, dpp_f32<kRowShr4>(ninf, x));
+    x = fmaxf(x, dpp_f32<kRowShr8>(ninf, x));
+    x = fmaxf(x, dpp_f32<kRowBcast15, 0xa>(ninf, x));
+    x = fmaxf(x, dpp_f32<kRowBcast31, 0xc>(ninf, x));
+    return read_lane(x, 63);
+}
+
+__device__ __forceinline__ int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+
+}  // namespace as

@@ -1,0 +1,253 @@
+// Lattice initialisation (Sec. 4.2, Definition "Arithmetic sampling") and the
+// synthetic low-rank bigram model that stands in for P(X_t | X_<t) (Sec. 3.3):
+// logits[r, v] = (scale/sqrt(d)) * sum_k E[prev[r], k] * U[k, v].
+//
+// The model keeps U transposed (Ut[V, d], K contiguous) so that both MFMA
+// operands are read as 16-byte K-runs; the logits GEMM is then an "NT" product
+// C[R, V] = gather(E, prev)[R, d] * Ut[V, d]^T on v_mfma_f32_32x32x16_bf16 with
+// fp32 accumulation.  It is the only dense contraction on the path.
+#include "as_common.hpp"
+
+namespace as {
+namespace {
+
+// ------------------------------------------------------------------ lattice
+
+__global__ void lattice_kernel(const float *u, int32_t B, int32_t N, float *codes,
+                               const int32_t *prompts, int32_t *prev, uint8_t *finished)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)B * N) return;
+    const int32_t b = (int32_t)(idx / N), i = (int32_t)(idx % N);
+    // c_i = (i + u)/N: spacing exactly 1/N around the circle, one shift per prompt
+    const double c = ((double)i + (double)u[b]) / (double)N;
+    codes[idx] = fminf((float)c, 0x1.fffffep-1f);
+    if (prev) prev[idx] = prompts[b];
+    if (finished) finished[idx] = 0;
+}
+
+// ---------------------------------------------------------------- transpose
+
+template <class T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *U, T *Ut, int32_t d, int32_t V)
+{
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+    const int64_t v0 = (int64_t)blockIdx.x * 32, k0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t k = k0 + ty + i * 8, v = v0 + tx;
+        if (k < d && v < V) tile[ty + i * 8][tx] = U[k * V + v];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t v = v0 + ty + i * 8, k = k0 + tx;
+        if (k < d && v < V) Ut[v * d + k] = tile[tx][ty + i * 8];
+    }
+}
+
+// -------------------------------------------------------------- logits GEMM
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDS_STRIDE = BK + 8;          // bf16 elements; +16 B keeps ds_read_b128 off one bank
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t b = __builtin_bit_cast(uint32_t, f);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+
+template <class OutT> __device__ __forceinline__ OutT to_out(float f);
+template <> __device__ __forceinline__ float to_out<float>(float f) { return f; }
+template <> __device__ __forceinline__ uint16_t to_out<uint16_t>(float f) { return f32_to_bf16_rne(f); }
+
+// C[R, V] tile BM x BN per block, 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA tiles.
+template <class OutT>
+__global__ __launch_bounds__(256) void bigram_gemm_bf16(const uint16_t *__restrict__ E,
+                                                        const uint16_t *__restrict__ Ut,
+                                                        const int32_t *__restrict__ prev, int64_t R,
+                                                        int32_t V, int32_t d, float alpha,
+                                                        OutT *__restrict__ C, int64_t ldc)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS_STRIDE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    // consecutive blocks walk the M direction first so that blocks running
+    // together share the same Ut tile through L2
+    const int64_t m_blocks = (R + BM - 1) / BM;
+    const int64_t bm = blockIdx.x % m_blocks, bn = blockIdx.x / m_blocks;
+    const int64_t m0 = bm * BM, n0 = bn * BN;
+
+    // each thread moves 4 + 4 sixteen-byte pieces per K step
+    const int prow = tid >> 3, pcol = (tid & 7) * 8;
+    const uint16_t *gA[4], *gB[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int64_t m = m0 + prow + i * 32;
+        if (m > R - 1) m = R - 1;
+        int64_t n = n0 + prow + i * 32;
+        if (n > V - 1) n = V - 1;
+        gA[i] = E + (int64_t)prev[m] * d + pcol;
+        gB[i] = Ut + n * d + pcol;
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    uint4 ra[4], rb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ra[i] = *reinterpret_cast<const uint4 *>(gA[i]);
+        rb[i] = *reinterpret_cast<const uint4 *>(gB[i]);
+    }
+
+    const int frow = lane & 31, fk = (lane >> 5) * 8;
+    for (int k0 = 0; k0 < d; k0 += BK) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<uint4 *>(&sA[(prow + i * 32) * LDS_STRIDE + pcol]) = ra[i];
+            *reinterpret_cast<uint4 *>(&sB[(prow + i * 32) * LDS_STRIDE + pcol]) = rb[i];
+        }
+        __syncthreads();
+        if (k0 + BK < d) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ra[i] = *reinterpret_cast<const uint4 *>(gA[i] + k0 + BK);
+                rb[i] = *reinterpret_cast<const uint4 *>(gB[i] + k0 + BK);
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            bf16x8 fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                fa[i] = *reinterpret_cast<const bf16x8 *>(&sA[(wm * 64 + i * 32 + frow) * LDS_STRIDE + kk + fk]);
+                fb[i] = *reinterpret_cast<const bf16x8 *>(&sB[(wn * 64 + i * 32 + frow) * LDS_STRIDE + kk + fk]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // D layout of the 32x32 MFMA: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (m < R && n < V) C[m * ldc + n] = to_out<OutT>(acc[i][j][v] * alpha);
+            }
+        }
+    }
+}
+
+// Plain dot products for what the MFMA kernel does not take: fp32 weights, or a
+// rank d that is not a multiple of its K step (small models only).
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(uint16_t h) { return __builtin_bit_cast(float, (uint32_t)h << 16); }
+
+template <class WT, class OutT>
+__global__ __launch_bounds__(256) void bigram_dot(const WT *__restrict__ E, const WT *__restrict__ Ut,
+                                                  const int32_t *__restrict__ prev, int64_t R, int32_t V,
+                                                  int32_t d, float alpha, OutT *__restrict__ C, int64_t ldc)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= R * V) return;
+    const int64_t r = idx / V, v = idx % V;
+    const WT *a = E + (int64_t)prev[r] * d, *b = Ut + v * d;
+    float acc = 0.f;
+    for (int k = 0; k < d; ++k) acc = fmaf(widen(a[k]), widen(b[k]), acc);
+    C[r * ldc + v] = to_out<OutT>(acc * alpha);
+}
+
+template <class WT, class OutT>
+void launch_dot(as_ctx *ctx, const as_model *m, const int32_t *prev, int64_t rows, void *out, int64_t ld,
+                float alpha)
+{
+    const int64_t n = rows * (int64_t)m->V;
+    launch(ctx, kKernelLogits, bigram_dot<WT, OutT>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+           (const WT *)m->E, (const WT *)m->Ut, prev, rows, m->V, m->d, alpha, (OutT *)out, ld);
+}
+
+}  // namespace
+
+as_status launch_lattice(as_ctx *ctx, const float *u, int32_t B, int32_t N, float *codes_out,
+                         const int32_t *prompts, int32_t *prev_out, uint8_t *finished_out)
+{
+    const int64_t n = (int64_t)B * N;
+    if (n == 0) return AS_OK;
+    hipLaunchKernelGGL(lattice_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, u, B, N,
+                       codes_out, prompts, prev_out, finished_out);
+    AS_HIP_TRY(ctx, hipGetLastError());
+    return AS_OK;
+}
+
+as_status launch_transpose(const void *U, void *Ut, int32_t d, int32_t V, as_dtype wdtype)
+{
+    const dim3 grid((unsigned)((V + 31) / 32), (unsigned)((d + 31) / 32));
+    if (wdtype == AS_BF16)
+        hipLaunchKernelGGL((transpose_kernel<uint16_t>), grid, dim3(256), 0, nullptr,
+                           (const uint16_t *)U, (uint16_t *)Ut, d, V);
+    else
+        hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(256), 0, nullptr, (const float *)U,
+                           (float *)Ut, d, V);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(nullptr, e, "transpose launch");
+    e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "transpose sync");
+    return AS_OK;
+}
+
+as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *prev, int64_t rows,
+                               void *logits_out, int64_t ld)
+{
+    if (rows == 0) return AS_OK;
+    const float alpha = (float)((double)m->scale / sqrt((double)m->d));
+    const bool mfma = m->wdtype == AS_BF16 && m->d % BK == 0 &&
+                      reinterpret_cast<uintptr_t>(m->E) % 16 == 0 && reinterpret_cast<uintptr_t>(m->Ut) % 16 == 0;
+    if (mfma) {
+        const int64_t blocks = ((rows + BM - 1) / BM) * (((int64_t)m->V + BN - 1) / BN);
+        if (blocks > 0x7fffffffLL) return fail(ctx, AS_ERR_UNSUPPORTED, "logits GEMM grid too large");
+        if (ctx->dtype == AS_BF16)
+            launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t>, dim3((unsigned)blocks), dim3(256), 0,
+                   (const uint16_t *)m->E, (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha,
+                   (uint16_t *)logits_out, ld);
+        else
+            launch(ctx, kKernelLogits, bigram_gemm_bf16<float>, dim3((unsigned)blocks), dim3(256), 0,
+                   (const uint16_t *)m->E, (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha,
+                   (float *)logits_out, ld);
+    } else {
+        if ((rows * (int64_t)m->V + 255) / 256 > 0x7fffffffLL)
+            return fail(ctx, AS_ERR_UNSUPPORTED, "logits grid too large");
+        if (m->wdtype == AS_BF16) {
+            if (ctx->dtype == AS_BF16) launch_dot<uint16_t, uint16_t>(ctx, m, prev, rows, logits_out, ld, alpha);
+            else launch_dot<uint16_t, float>(ctx, m, prev, rows, logits_out, ld, alpha);
+        } else {
+            if (ctx->dtype == AS_BF16) launch_dot<float, uint16_t>(ctx, m, prev, rows, logits_out, ld, alpha);
+            else launch_dot<float, float>(ctx, m, prev, rows, logits_out, ld, alpha);
+        }
+    }
+    AS_HIP_TRY(ctx, hipGetLastError());
+    return AS_OK;
+}
+
+}  // namespace as

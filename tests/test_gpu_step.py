@@ -1,0 +1,138 @@
+"""GPU parity of the fused sampling step (as_step / as_step_ex) against the CPU
+oracle, element by element on the same seeded inputs, through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2210_15458_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(V, R, dtype, temp=1.0, top_k=0, top_p=1.0, ld=None, sigma=3.0, seed=3, label=None, **kw):
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    stored = synth.gaussian_logits(R, V, sigma=sigma, seed=seed, dtype=dtype, ld=ld)
+    codes = synth.uniform_codes(R, seed=seed + 1)
+    label = label or f"V={V} R={R} {dtype} temp={temp} k={top_k} p={top_p} ld={ld}"
+    print("case", label, flush=True)
+    gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, **kw)
+    ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, **kw)
+    stats = compare_step(gpu, ref, V, label, trunc=(top_k > 0 or top_p < 1.0))
+    print("   ", stats, flush=True)
+    return gpu, ref, stats
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("temp", [0.7, 1.0])
+def test_step_headline_vocab(dtype, temp):
+    _check(32128, 96, dtype, temp=temp)
+
+
+@pytest.mark.parametrize("V,ld", [(1, None), (5, None), (16, None), (511, None), (1000, None), (1001, None),
+                                  (1001, 1008), (4097, 4104), (32771, 32776), (32768, None), (40000, 40003)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_ragged_vocab_and_padding(V, ld, dtype):
+    # odd V without padding gives rows that do not start on 16 bytes: element path
+    _check(V, 33, dtype, ld=ld, seed=V)
+
+
+@pytest.mark.parametrize("V,dtype", [(256000, "bf16"), (70001, "f32"), (131072, "bf16"), (300000, "f32")])
+def test_step_multi_tile_rows(V, dtype):
+    _check(V, 12, dtype, seed=11)
+
+
+@pytest.mark.parametrize("sigma,temp", [(0.01, 1.0), (10.0, 0.3), (3.0, 50.0), (30.0, 1.0)])
+def test_step_flat_and_peaked_rows(sigma, temp):
+    _check(32128, 48, "bf16", temp=temp, sigma=sigma, seed=5)
+    _check(5000, 48, "f32", temp=temp, sigma=sigma, seed=6)
+
+
+def test_step_special_rows_and_codes():
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    V, R = 3000, 8
+    x = synth.bf16_bits_to_f32(synth.gaussian_logits(R, V, seed=9, dtype="bf16")).copy()
+    x[0, :] = -np.inf; x[0, 1234] = 0.5              # one-hot
+    x[1, :] = 0.0                                      # uniform
+    x[2, ::2] = -np.inf                                # every other token impossible
+    x[3, : V - 1] = -np.inf                            # only the last token
+    x[4, 1:] = -np.inf                                 # only the first token
+    x[5, :] = -80.0; x[5, 7] = 80.0                    # huge dynamic range
+    codes = np.array([0.37, 0.5, 0.999, 0.0, 1 - 2.0 ** -24, 0.25, 0.0, 1 - 2.0 ** -24], np.float32)
+    for dtype in ("bf16", "f32"):
+        stored = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+        gpu = run_gpu_step(stored, codes, V)
+        ref = oracle_step(stored, codes, V)
+        print(dtype, compare_step(gpu, ref, V, f"special {dtype}"), flush=True)
+        assert gpu["token"][0] == 1234 and gpu["token"][3] == V - 1 and gpu["token"][4] == 0
+        assert gpu["token"][6] == ref["token"][6] and gpu["token"][7] == ref["token"][7]
+
+
+def test_step_finished_rows_eos_and_row_ids():
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    V, LR, R = 2048, 5, 40
+    rng = np.random.default_rng(12)
+    stored = synth.gaussian_logits(LR, V, seed=13, dtype="bf16")
+    wide = synth.bf16_bits_to_f32(stored).copy()
+    wide[:, 1] += 14.0                                  # make EOS (id 1) likely
+    stored = synth.f32_to_bf16_bits(wide)
+    codes = synth.uniform_codes(R, seed=14)
+    rid = rng.integers(0, LR, R).astype(np.int32)
+    fin = (rng.random(R) < 0.3).astype(np.uint8)
+    gpu = run_gpu_step(stored, codes, V, finished=fin, eos_id=1, row_ids=rid)
+    ref = oracle_step(stored, codes, V, finished=fin, eos_id=1, row_ids=rid.astype(np.int64))
+    print(compare_step(gpu, ref, V, "finished/row_ids"), flush=True)
+    assert np.all(gpu["token"][fin == 1] == 1)
+    assert np.array_equal(gpu["c_next"][fin == 1], codes[fin == 1])       # code untouched
+    assert np.all(gpu["finished"][fin == 1] == 1)
+    assert np.array_equal(gpu["finished"], ref["finished"])
+    assert (gpu["finished"][fin == 0] == 1).any()                          # some row emitted EOS now
+
+
+def test_step_is_deterministic_and_in_place():
+    import torch
+    from paper_2210_15458_amd import binding as B
+    from gpu_util import to_dev_logits
+    V, R = 32128, 64
+    logits = to_dev_logits(synth.gaussian_logits(R, V, seed=21, dtype="bf16"))
+    codes = torch.from_numpy(synth.uniform_codes(R, seed=22)).cuda()
+    ctx = B.Ctx(R, V, logits.dtype)
+    outs = []
+    for _ in range(3):
+        tok = torch.empty(R, dtype=torch.int32, device="cuda")
+        c = codes.clone()
+        B.as_step(ctx, logits, c, 0.9, 0, 1.0, tok, c)                      # codes_out aliases codes
+        torch.cuda.synchronize()
+        outs.append((tok.cpu().numpy(), c.cpu().numpy()))
+    for t, c in outs[1:]:
+        assert np.array_equal(t, outs[0][0]) and np.array_equal(c, outs[0][1])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("top_k,top_p,temp", [(40, 1.0, 1.0), (0, 0.9, 1.0), (1, 1.0, 1.0), (5, 0.5, 0.7),
+                                              (1000, 0.95, 1.3), (0, 0.3, 0.8)])
+def test_step_truncation(dtype, top_k, top_p, temp):
+    _check(32128, 64, dtype, temp=temp, top_k=top_k, top_p=top_p, seed=31)
+    _check(1001, 40, dtype, temp=temp, top_k=min(top_k, 900), top_p=top_p, seed=32)
+
+
+def test_step_truncation_multi_tile():
+    _check(256000, 6, "bf16", top_k=40, seed=33)
+    _check(256000, 6, "bf16", top_p=0.9, seed=34)
+
+
+def test_step_argument_errors():
+    import torch
+    from paper_2210_15458_amd import binding as B
+    ctx = B.Ctx(8, 100, torch.float32)
+    logits = torch.zeros(8, 100, device="cuda")
+    codes = torch.zeros(8, device="cuda")
+    tok = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.ArithSamplingError) as e:
+        B.as_step(ctx, logits, codes, 0.0, 0, 1.0, tok, codes)
+    assert e.value.code == 1 and "temp" in str(e.value)
+    with pytest.raises(B.ArithSamplingError):
+        B.as_step(ctx, torch.zeros(8, 64, device="cuda"), codes, 1.0, 0, 1.0, tok, codes)   # ld < V
+    with pytest.raises(B.ArithSamplingError):
+        B.as_step(ctx, torch.zeros(9, 100, device="cuda"), torch.zeros(9, device="cuda"), 1.0, 0, 1.0,
+                  torch.zeros(9, dtype=torch.int32, device="cuda"), torch.zeros(9, device="cuda"))  # rows > max
+    B.as_step(ctx, logits[:0], codes[:0], 1.0, 0, 1.0, tok[:0], codes[:0])                  # empty batch is fine
+    ctx.close()
