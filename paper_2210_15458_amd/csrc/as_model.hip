@@ -6,6 +6,8 @@
 // operands are read as 16-byte K-runs; the logits GEMM is then an "NT" product
 // C[R, V] = gather(E, prev)[R, d] * Ut[V, d]^T on v_mfma_f32_32x32x16_bf16 with
 // fp32 accumulation.  It is the only dense contraction on the path.
+#include <type_traits>
+
 #include "as_common.hpp"
 
 namespace as {
@@ -51,9 +53,13 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *U, T *Ut, int32
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDS_STRIDE = BK + 8;          // bf16 elements; +16 B keeps ds_read_b128 off one bank
+// Block tile BM x BN, K step BK; 4 waves as 2 (M) x 2 (N), each wave 64 x 128 =
+// 2 x 4 MFMA tiles of 32 x 32 (128 accumulator registers per lane).
+constexpr int BM = 128, BN = 256, BK = 64;
+constexpr int kPieces = BK / 8;                       // 16-byte pieces per tile row
+constexpr int kStageRows = 32;                        // C rows staged per epilogue pass
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
@@ -66,98 +72,142 @@ template <class OutT> __device__ __forceinline__ OutT to_out(float f);
 template <> __device__ __forceinline__ float to_out<float>(float f) { return f; }
 template <> __device__ __forceinline__ uint16_t to_out<uint16_t>(float f) { return f32_to_bf16_rne(f); }
 
-// C[R, V] tile BM x BN per block, 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA tiles.
+// Byte offset of 16-byte piece c of tile row `row`: pieces of a row are permuted
+// by the row's low bits so that 8 lanes reading the same piece index of 8
+// consecutive rows (an MFMA fragment read) touch all LDS banks once.
+__device__ __forceinline__ int swz(int row, int c) { return row * (BK * 2) + ((c ^ (row & 7)) << 4); }
+
 template <class OutT>
-__global__ __launch_bounds__(256) void bigram_gemm_bf16(const uint16_t *__restrict__ E,
-                                                        const uint16_t *__restrict__ Ut,
-                                                        const int32_t *__restrict__ prev, int64_t R,
-                                                        int32_t V, int32_t d, float alpha,
-                                                        OutT *__restrict__ C, int64_t ldc)
+__global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__restrict__ E,
+                                                           const uint16_t *__restrict__ Ut,
+                                                           const int32_t *__restrict__ prev, int64_t R,
+                                                           int32_t V, int32_t d, float alpha,
+                                                           OutT *__restrict__ C, int64_t ldc, int vec_store)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS_STRIDE];
+    constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2;
+    constexpr int kStageStride = BN * (int)sizeof(OutT) + 16;          // bytes per staged C row
+    constexpr int kStageBytes = kStageRows * kStageStride;
+    constexpr int kLds = (kABytes + kBBytes) > kStageBytes ? (kABytes + kBBytes) : kStageBytes;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kLds];
+    unsigned char *sA = smem, *sB = smem + kABytes;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    // consecutive blocks walk the M direction first so that blocks running
-    // together share the same Ut tile through L2
+
+    // Work-groups are handed to the 8 XCDs round-robin.  Give each XCD whole
+    // column tiles and let it walk the row tiles of one column tile back to
+    // back, so the Ut tile they share is fetched into that XCD's L2 once.
     const int64_t m_blocks = (R + BM - 1) / BM;
-    const int64_t bm = blockIdx.x % m_blocks, bn = blockIdx.x / m_blocks;
+    const int64_t n_blocks = ((int64_t)V + BN - 1) / BN;
+    const int64_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int64_t bn = xcd + 8 * (slot / m_blocks), bm = slot % m_blocks;
+    if (bn >= n_blocks) return;
     const int64_t m0 = bm * BM, n0 = bn * BN;
 
-    // each thread moves 4 + 4 sixteen-byte pieces per K step
-    const int prow = tid >> 3, pcol = (tid & 7) * 8;
-    const uint16_t *gA[4], *gB[4];
+    // global -> register -> LDS: 4 pieces of A and 8 of B per thread and K step
+    const int prow = tid >> 3, pc = tid & 7;
+    const uint16_t *gA[4], *gB[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int64_t m = m0 + prow + i * 32;
         if (m > R - 1) m = R - 1;
+        gA[i] = E + (int64_t)prev[m] * d + pc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
         int64_t n = n0 + prow + i * 32;
         if (n > V - 1) n = V - 1;
-        gA[i] = E + (int64_t)prev[m] * d + pcol;
-        gB[i] = Ut + n * d + pcol;
+        gB[i] = Ut + n * d + pc * 8;
     }
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][4];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 ra[4], rb[4];
+    u32x4 ra[4], rb[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        ra[i] = *reinterpret_cast<const uint4 *>(gA[i]);
-        rb[i] = *reinterpret_cast<const uint4 *>(gB[i]);
-    }
+    for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const u32x4 *>(gA[i]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(gB[i]);
 
-    const int frow = lane & 31, fk = (lane >> 5) * 8;
+    const int frow = lane & 31, fc = lane >> 5;
     for (int k0 = 0; k0 < d; k0 += BK) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<uint4 *>(&sA[(prow + i * 32) * LDS_STRIDE + pcol]) = ra[i];
-            *reinterpret_cast<uint4 *>(&sB[(prow + i * 32) * LDS_STRIDE + pcol]) = rb[i];
-        }
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(sA + swz(prow + i * 32, pc)) = ra[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4 *>(sB + swz(prow + i * 32, pc)) = rb[i];
         __syncthreads();
         if (k0 + BK < d) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                ra[i] = *reinterpret_cast<const uint4 *>(gA[i] + k0 + BK);
-                rb[i] = *reinterpret_cast<const uint4 *>(gB[i] + k0 + BK);
-            }
+            for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const u32x4 *>(gA[i] + k0 + BK);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(gB[i] + k0 + BK);
         }
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8 fa[2], fb[2];
+        for (int kk = 0; kk < kPieces; kk += 2) {
+            bf16x8 fa[2], fb[4];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                fa[i] = *reinterpret_cast<const bf16x8 *>(&sA[(wm * 64 + i * 32 + frow) * LDS_STRIDE + kk + fk]);
-                fb[i] = *reinterpret_cast<const bf16x8 *>(&sB[(wn * 64 + i * 32 + frow) * LDS_STRIDE + kk + fk]);
-            }
+            for (int i = 0; i < 2; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8 *>(sA + swz(wm * 64 + i * 32 + frow, kk + fc));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8 *>(sB + swz(wn * 128 + j * 32 + frow, kk + fc));
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
     }
 
-    // D layout of the 32x32 MFMA: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    // Epilogue: scale, round once to the storage type, stage 32 rows at a time in
+    // LDS and write them out as whole 16-byte pieces along the row.
+    // D layout of the 32x32 MFMA: register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    constexpr int kOutPerPiece = 16 / (int)sizeof(OutT);
+    constexpr int kPiecesPerRow = BN / kOutPerPiece;
+    auto do_pass = [&](auto pass_c) {
+        constexpr int pass = decltype(pass_c)::value;
+        constexpr int i = pass & 1;
+        __syncthreads();
+        if (wm == pass / 2) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+            for (int j = 0; j < 4; ++j) {
+                const int col = wn * 128 + j * 32 + (lane & 31);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (m < R && n < V) C[m * ldc + n] = to_out<OutT>(acc[i][j][v] * alpha);
+                for (int v = 0; v < 16; ++v) {
+                    const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    *reinterpret_cast<OutT *>(smem + row * kStageStride + col * (int)sizeof(OutT)) =
+                        to_out<OutT>(acc[i][j][v] * alpha);
+                }
             }
         }
-    }
+        __syncthreads();
+        for (int p = tid; p < kStageRows * kPiecesPerRow; p += 256) {
+            const int row = p / kPiecesPerRow, pcol = p % kPiecesPerRow;
+            const int64_t m = m0 + pass * kStageRows + row;
+            const int64_t n = n0 + (int64_t)pcol * kOutPerPiece;
+            if (m >= R || n >= V) continue;
+            const unsigned char *sp = smem + row * kStageStride + pcol * 16;
+            OutT *gp = C + m * ldc + n;
+            if (vec_store && n + kOutPerPiece <= V) {
+                *reinterpret_cast<u32x4 *>(gp) = *reinterpret_cast<const u32x4 *>(sp);
+            } else {
+                const OutT *se = reinterpret_cast<const OutT *>(sp);
+                for (int e = 0; e < kOutPerPiece; ++e)
+                    if (n + e < V) gp[e] = se[e];
+            }
+        }
+    };
+    static_assert(BM / kStageRows == 4, "epilogue passes are spelled out");
+    do_pass(std::integral_constant<int, 0>{});
+    do_pass(std::integral_constant<int, 1>{});
+    do_pass(std::integral_constant<int, 2>{});
+    do_pass(std::integral_constant<int, 3>{});
 }
 
 // Plain dot products for what the MFMA kernel does not take: fp32 weights, or a
@@ -225,16 +275,20 @@ as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *pr
     const bool mfma = m->wdtype == AS_BF16 && m->d % BK == 0 &&
                       reinterpret_cast<uintptr_t>(m->E) % 16 == 0 && reinterpret_cast<uintptr_t>(m->Ut) % 16 == 0;
     if (mfma) {
-        const int64_t blocks = ((rows + BM - 1) / BM) * (((int64_t)m->V + BN - 1) / BN);
+        // grid: 8 XCD lanes x ceil(column tiles / 8) x row tiles (see the kernel's tile mapping)
+        const int64_t m_blocks = (rows + BM - 1) / BM, n_blocks = ((int64_t)m->V + BN - 1) / BN;
+        const int64_t blocks = 8 * ((n_blocks + 7) / 8) * m_blocks;
         if (blocks > 0x7fffffffLL) return fail(ctx, AS_ERR_UNSUPPORTED, "logits GEMM grid too large");
+        const size_t osz = ctx->dtype == AS_BF16 ? 2 : 4;
+        const int vec_store = (reinterpret_cast<uintptr_t>(logits_out) % 16 == 0) && ((ld * osz) % 16 == 0);
         if (ctx->dtype == AS_BF16)
             launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t>, dim3((unsigned)blocks), dim3(256), 0,
                    (const uint16_t *)m->E, (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha,
-                   (uint16_t *)logits_out, ld);
+                   (uint16_t *)logits_out, ld, vec_store);
         else
             launch(ctx, kKernelLogits, bigram_gemm_bf16<float>, dim3((unsigned)blocks), dim3(256), 0,
                    (const uint16_t *)m->E, (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha,
-                   (float *)logits_out, ld);
+                   (float *)logits_out, ld, vec_store);
     } else {
         if ((rows * (int64_t)m->V + 255) / 256 > 0x7fffffffLL)
             return fail(ctx, AS_ERR_UNSUPPORTED, "logits grid too large");
