@@ -2,6 +2,7 @@
 // the context's stream.  No entry point synchronises the device except
 // as_ctx_destroy and as_model_create_bigram / as_model_destroy.
 #include <math.h>
+#include <stdlib.h>
 
 #include <new>
 
@@ -109,6 +110,7 @@ as_status as_ctx_create(as_ctx **out, int64_t max_rows, int32_t V, as_dtype logi
     c->max_rows = max_rows;
     c->V = V;
     c->dtype = logits_dtype;
+    if (const char *shape = getenv("AS_STEP_SHAPE")) c->step_shape = atoi(shape);
     e = hipMalloc(reinterpret_cast<void **>(&c->thr), (size_t)max_rows * sizeof(float));
     if (e != hipSuccess) {
         (void)hipGetLastError();
