@@ -187,7 +187,7 @@ as_status as_step_ex(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, 
     }
     StepArgs a{};
     a.logits = logits; a.rows = rows; a.ld = ld; a.V = ctx->V; a.dtype = ctx->dtype;
-    a.codes = codes; a.temp = temp; a.thr = thr;
+    a.codes = codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = thr;
     a.tokens_out = tokens_out; a.tok_stride = 1; a.codes_out = codes_out;
     a.finished_in = finished_in; a.eos_id = eos_id; a.finished_out = finished_out;
     a.prob_out = prob_out; a.flo_out = flo_out; a.row_ids = row_ids; a.prev_out = nullptr;
@@ -302,7 +302,7 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, 
         }
         StepArgs a{};
         a.logits = ctx->logits.ptr; a.rows = R; a.ld = ldw; a.V = ctx->V; a.dtype = ctx->dtype;
-        a.codes = codes; a.temp = temp; a.thr = trunc ? ctx->thr : nullptr;
+        a.codes = codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = trunc ? ctx->thr : nullptr;
         a.tokens_out = tokens_out + t; a.tok_stride = T; a.codes_out = codes;
         a.finished_in = eos_id >= 0 ? fin : nullptr; a.eos_id = eos_id;
         a.finished_out = eos_id >= 0 ? fin : nullptr;

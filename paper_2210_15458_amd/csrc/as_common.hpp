@@ -101,6 +101,7 @@ struct StepArgs {
     as_dtype dtype;
     const float *codes;
     float temp;
+    float k;                     // log2(e)/temp, computed once on the host
     const float *thr;            // per-row keep threshold on raw logits, or null
     int32_t *tokens_out;
     int64_t tok_stride;          // tokens_out[r * tok_stride]
@@ -188,18 +189,48 @@ __device__ __forceinline__ double read_lane(double x, int lane)
 }
 
 // Sum / max over the wave, result in every lane (wave-uniform).
-__device__ __forceinline__ float wave_sum(float x) { return read_lane(wave_scan_add(x), 63); }
+// Written as six fused DPP instructions: destination and both sources are the
+// same register, so a lane without a valid source (or masked off by row_mask)
+// simply keeps its value, which is the identity for both operations.  A VALU
+// write needs two wait states before a DPP read of the same register.
+__device__ __forceinline__ float wave_sum(float x)
+{
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 0"
+        : "+v"(x));
+    return read_lane(x, 63);
+}
 __device__ __forceinline__ double wave_sum(double x) { return read_lane(wave_scan_add(x), 63); }
 
 __device__ __forceinline__ float wave_max(float x)
 {
-    const float ninf = -__builtin_inff();
-    x = fmaxf(x, dpp_f32<kRowShr1>(ninf, x));
-    x = fmaxf(x, dpp_f32<kRowShr2>(ninf, x));
-    x = fmaxf(x, dpp_f32<kRowShr4>(ninf, x));
-    x = fmaxf(x, dpp_f32<kRowShr8>(ninf, x));
-    x = fmaxf(x, dpp_f32<kRowBcast15, 0xa>(ninf, x));
-    x = fmaxf(x, dpp_f32<kRowBcast31, 0xc>(ninf, x));
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 0"
+        : "+v"(x));
     return read_lane(x, 63);
 }
 
