@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold (rotating buffers) kernel leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of a known size (256 MiB each), the yardstick for "
+                         "reading rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (codes are independent, so more GPUs would each "
@@ -74,23 +77,25 @@ def main():
     for _ in range(args.warmup):
         decode()
     torch.cuda.synchronize()
-    ctx.profile(True)
+    # timed region: K whole decodes, nothing else on the stream
     t0 = time.perf_counter()
     for _ in range(args.steps):
         decode()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    step_ms, step_n, step_drop = ctx.profile_read(0)
-    gemm_ms, gemm_n, _ = ctx.profile_read(1)
-    thr_ms, thr_n, _ = ctx.profile_read(2)
-    ctx.profile(False)
 
-    # same region once more without per-dispatch events, to show what they cost
+    # the same region once more with a start/stop event attached to every kernel
+    # dispatch (this costs some launch throughput, so it is kept out of `value`)
+    ctx.profile(True)
     t2 = time.perf_counter()
     for _ in range(args.steps):
         decode()
     torch.cuda.synchronize()
     t3 = time.perf_counter()
+    step_ms, step_n, step_drop = ctx.profile_read(0)
+    gemm_ms, gemm_n, _ = ctx.profile_read(1)
+    thr_ms, thr_n, _ = ctx.profile_read(2)
+    ctx.profile(False)
 
     wall = t1 - t0
     code_steps = R * T * args.steps
@@ -121,7 +126,7 @@ def main():
                                f"weights+logits, B={Bn} N={N} (R={R}) T={T} temp={temp} top_k={top_k} "
                                f"top_p={top_p} eos={eos}; one step = one whole decode ({R * T} code-steps)",
                    "storage": cfg["dtype"], "rows": R, "decode_steps": T,
-                   "value_without_dispatch_events": code_steps / (t3 - t2)},
+                   "value_with_dispatch_events": code_steps / (t3 - t2)},
         "roofline": {
             "kernel": "step_kernel (fused sampling step), as launched inside as_decode",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -139,6 +144,24 @@ def main():
         out["logits_gemm"]["frac"] = out["logits_gemm"]["achieved"] / MFMA_BF16_PEAK_TFLOPS
     if thr_n:
         out["threshold_kernel"] = {"avg_launch_us": thr_ms / thr_n * 1e3, "launches": thr_n}
+
+    if args.copy_calibration:
+        src_t = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda").random_()
+        dst_t = torch.empty_like(src_t)
+        for _ in range(10):
+            dst_t.copy_(src_t)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read_per_launch": src_t.numel(), "bytes_written_per_launch": src_t.numel(),
+                                   "launches": 10}
+        del src_t, dst_t
+
+    # ---- measured HBM traffic of the sampling kernel, if a counter run has been recorded
+    traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "step_kernel_traffic.json")
+    if os.path.exists(traffic_file) and args.config == 1:
+        with open(traffic_file) as f:
+            tr = json.load(f)
+        out["roofline"]["traffic"] = tr.get("traffic_bytes_per_launch")
+        out["roofline"]["traffic_source"] = tr.get("source")
 
     # ---- cold leg: the sampling kernel alone, rotating over > 1 GiB of logits
     if not args.no_cold:
@@ -192,7 +215,7 @@ def main():
             oracle.step(stored[:sample_rows], codes[:sample_rows], temp=temp, top_k=top_k, top_p=top_p, V=V,
                         nthreads=nthreads)
             reps += 1
-            if time.perf_counter() - c0 > 1.5 or reps >= 16:
+            if time.perf_counter() - c0 > 1.5:
                 break
         c1 = time.perf_counter()
         out["cpu_baseline"] = {
