@@ -43,6 +43,9 @@
 
 #include "as_common.hpp"
 
+#ifndef AS_STEP_AHEAD
+#define AS_STEP_AHEAD 4
+#endif
 #ifndef AS_STEP_GROUP
 #define AS_STEP_GROUP 4
 #endif
@@ -246,16 +249,25 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
             mych = mych < 0 ? 0 : (mych > ITERS ? ITERS : mych);
             off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
         }
+        // A wave issues in order: while a load waits for room in the memory pipeline the wave
+        // cannot start on data it already has.  So only AHEAD groups are requested up front
+        // and group g+AHEAD is requested right after group g has been consumed.
+        constexpr int AHEAD = AS_STEP_AHEAD < NG ? AS_STEP_AHEAD : NG;
+        auto request = [&](int g) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < ITERS; ++j) {
-            uint32_t off = off0 + (uint32_t)j * 1024u;
-            if constexpr (RAGGED) off = off < off_last ? off : off_last;
-            // streamed once: non-temporal, so the row does not push other data out of L2
-            raw[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
-            // keep the requests in vocabulary order and ahead of all arithmetic:
-            // the consumer waits for them one by one, in this order
+            for (int jj = 0; jj < G; ++jj) {
+                const int j = g * G + jj;
+                uint32_t off = off0 + (uint32_t)j * 1024u;
+                if constexpr (RAGGED) off = off < off_last ? off : off_last;
+                // streamed once: non-temporal, so the row does not push other data out of L2
+                raw[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+            }
+            // keep the requests in vocabulary order and where they are written: the consumer
+            // waits for them one by one, in this order
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+#pragma unroll
+        for (int g = 0; g < AHEAD; ++g) request(g);
         float TL = 0.f, RL = kRefFloor;
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
@@ -291,6 +303,10 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
             rgl[g] = RLn;
             TL = ldexpf(TL, shift_of(RL, RLn)) + gs;
             RL = RLn;
+            if (g + AHEAD < NG) {
+                __builtin_amdgcn_sched_barrier(0);
+                request(g + AHEAD);
+            }
         }
         const float rW = wave_max(RL);
         const float W = wave_sum(ldexpf(TL, shift_of(RL, rW)));
@@ -486,8 +502,13 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
     RowOut o;
     o.token = (int32_t)tok64;
     o.c_next = rescale_code(tau, before, ev);
-    o.prob = (float)(ev / S);
-    o.f_lo = (float)(before / S);
+    o.prob = 0.f;
+    o.f_lo = 0.f;
+    if (a.prob_out || a.flo_out) {          // records for tests and callers that ask: fp32 quotients of fp64 sums
+        const float Sf = (float)S;
+        o.prob = (float)ev / Sf;
+        o.f_lo = (float)before / Sf;
+    }
     write_row(a, r, o);
 }
 
