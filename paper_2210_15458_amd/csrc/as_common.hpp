@@ -53,6 +53,7 @@ struct as_ctx {
     as::DeviceBuf state;           // codes f32[rows] | prev i32[rows] | finished u8[rows]
     as::Profile prof;
     int step_shape = 0;            // work-group shape of the sampling kernel (tuning knob, 0 = default)
+    int gemm_shape = 0;            // tile shape of the logits kernel (tuning knob, 0 = default)
     std::string err;
 };
 

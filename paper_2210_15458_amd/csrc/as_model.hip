@@ -57,7 +57,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Block tile BM x BN, K step BK; 4 waves as 2 (M) x 2 (N), each wave 64 x 128 =
 // 2 x 4 MFMA tiles of 32 x 32 (128 accumulator registers per lane).
-constexpr int BM = 128, BN = 256, BK = 64;
+constexpr int BM = 128, BK = 64;
 constexpr int kPieces = BK / 8;                       // 16-byte pieces per tile row
 constexpr int kStageRows = 32;                        // C rows staged per epilogue pass
 
@@ -75,16 +75,31 @@ template <> __device__ __forceinline__ uint16_t to_out<uint16_t>(float f) { retu
 // Byte offset of 16-byte piece c of tile row `row`: pieces of a row are permuted
 // by the row's low bits so that 8 lanes reading the same piece index of 8
 // consecutive rows (an MFMA fragment read) touch all LDS banks once.
-__device__ __forceinline__ int swz(int row, int c) { return row * (BK * 2) + ((c ^ (row & 7)) << 4); }
+#ifndef AS_GEMM_SWZ
+#define AS_GEMM_SWZ 1
+#endif
+__device__ __forceinline__ int swz(int row, int c)
+{
+#if AS_GEMM_SWZ == 0
+    return row * (BK * 2) + ((c ^ (row & 7)) << 4);
+#elif AS_GEMM_SWZ == 1
+    return row * (BK * 2) + ((c ^ ((row >> 1) & 7)) << 4);
+#else
+    return row * (BK * 2 + 16) + (c << 4);
+#endif
+}
 
-template <class OutT>
-__global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__restrict__ E,
+template <class OutT, int WNT, int OCC>
+__global__ __launch_bounds__(256, OCC) void bigram_gemm_bf16(const uint16_t *__restrict__ E,
                                                            const uint16_t *__restrict__ Ut,
                                                            const int32_t *__restrict__ prev, int64_t R,
                                                            int32_t V, int32_t d, float alpha,
                                                            OutT *__restrict__ C, int64_t ldc, int vec_store)
 {
-    constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2;
+    constexpr int BN = 2 * WNT * 32;                   // 2 waves along N, WNT MFMA tiles each
+    constexpr int kBPieces = BN / 32;                  // 16-byte pieces of B per thread and K step
+    constexpr int kRowBytes = (AS_GEMM_SWZ == 2) ? BK * 2 + 16 : BK * 2;
+    constexpr int kABytes = BM * kRowBytes, kBBytes = BN * kRowBytes;
     constexpr int kStageStride = BN * (int)sizeof(OutT) + 16;          // bytes per staged C row
     constexpr int kStageBytes = kStageRows * kStageStride;
     constexpr int kLds = (kABytes + kBBytes) > kStageBytes ? (kABytes + kBBytes) : kStageBytes;
@@ -106,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__res
 
     // global -> register -> LDS: 4 pieces of A and 8 of B per thread and K step
     const int prow = tid >> 3, pc = tid & 7;
-    const uint16_t *gA[4], *gB[8];
+    const uint16_t *gA[4], *gB[kBPieces];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int64_t m = m0 + prow + i * 32;
@@ -114,25 +129,25 @@ __global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__res
         gA[i] = E + (int64_t)prev[m] * d + pc * 8;
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < kBPieces; ++i) {
         int64_t n = n0 + prow + i * 32;
         if (n > V - 1) n = V - 1;
         gB[i] = Ut + n * d + pc * 8;
     }
 
-    f32x16 acc[2][4];
+    f32x16 acc[2][WNT];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < WNT; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    u32x4 ra[4], rb[8];
+    u32x4 ra[4], rb[kBPieces];
 #pragma unroll
     for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const u32x4 *>(gA[i]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(gB[i]);
+    for (int i = 0; i < kBPieces; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(gB[i]);
 
     const int frow = lane & 31, fc = lane >> 5;
     for (int k0 = 0; k0 < d; k0 += BK) {
@@ -140,27 +155,27 @@ __global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__res
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(sA + swz(prow + i * 32, pc)) = ra[i];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4 *>(sB + swz(prow + i * 32, pc)) = rb[i];
+        for (int i = 0; i < kBPieces; ++i) *reinterpret_cast<u32x4 *>(sB + swz(prow + i * 32, pc)) = rb[i];
         __syncthreads();
         if (k0 + BK < d) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const u32x4 *>(gA[i] + k0 + BK);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(gB[i] + k0 + BK);
+            for (int i = 0; i < kBPieces; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(gB[i] + k0 + BK);
         }
 #pragma unroll
         for (int kk = 0; kk < kPieces; kk += 2) {
-            bf16x8 fa[2], fb[4];
+            bf16x8 fa[2], fb[WNT];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
                 fa[i] = *reinterpret_cast<const bf16x8 *>(sA + swz(wm * 64 + i * 32 + frow, kk + fc));
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8 *>(sB + swz(wn * 128 + j * 32 + frow, kk + fc));
+            for (int j = 0; j < WNT; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8 *>(sB + swz(wn * (WNT * 32) + j * 32 + frow, kk + fc));
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < WNT; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
     }
@@ -176,8 +191,8 @@ __global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__res
         __syncthreads();
         if (wm == pass / 2) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int col = wn * 128 + j * 32 + (lane & 31);
+            for (int j = 0; j < WNT; ++j) {
+                const int col = wn * (WNT * 32) + j * 32 + (lane & 31);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -276,19 +291,30 @@ as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *pr
                       reinterpret_cast<uintptr_t>(m->E) % 16 == 0 && reinterpret_cast<uintptr_t>(m->Ut) % 16 == 0;
     if (mfma) {
         // grid: 8 XCD lanes x ceil(column tiles / 8) x row tiles (see the kernel's tile mapping)
+        const int shape = ctx->gemm_shape;
+        const int BN = shape == 1 ? 128 : 256;
         const int64_t m_blocks = (rows + BM - 1) / BM, n_blocks = ((int64_t)m->V + BN - 1) / BN;
         const int64_t blocks = 8 * ((n_blocks + 7) / 8) * m_blocks;
         if (blocks > 0x7fffffffLL) return fail(ctx, AS_ERR_UNSUPPORTED, "logits GEMM grid too large");
         const size_t osz = ctx->dtype == AS_BF16 ? 2 : 4;
         const int vec_store = (reinterpret_cast<uintptr_t>(logits_out) % 16 == 0) && ((ld * osz) % 16 == 0);
-        if (ctx->dtype == AS_BF16)
-            launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t>, dim3((unsigned)blocks), dim3(256), 0,
-                   (const uint16_t *)m->E, (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha,
-                   (uint16_t *)logits_out, ld, vec_store);
-        else
-            launch(ctx, kKernelLogits, bigram_gemm_bf16<float>, dim3((unsigned)blocks), dim3(256), 0,
-                   (const uint16_t *)m->E, (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha,
-                   (float *)logits_out, ld, vec_store);
+        const dim3 grid((unsigned)blocks), block(256);
+        const uint16_t *Ep = (const uint16_t *)m->E, *Up = (const uint16_t *)m->Ut;
+        if (ctx->dtype == AS_BF16) {
+            if (shape == 1)
+                launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t, 2, 4>, grid, block, 0, Ep, Up, prev, rows, m->V,
+                       m->d, alpha, (uint16_t *)logits_out, ld, vec_store);
+            else
+                launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t, 4, 2>, grid, block, 0, Ep, Up, prev, rows, m->V,
+                       m->d, alpha, (uint16_t *)logits_out, ld, vec_store);
+        } else {
+            if (shape == 1)
+                launch(ctx, kKernelLogits, bigram_gemm_bf16<float, 2, 4>, grid, block, 0, Ep, Up, prev, rows, m->V,
+                       m->d, alpha, (float *)logits_out, ld, vec_store);
+            else
+                launch(ctx, kKernelLogits, bigram_gemm_bf16<float, 4, 2>, grid, block, 0, Ep, Up, prev, rows, m->V,
+                       m->d, alpha, (float *)logits_out, ld, vec_store);
+        }
     } else {
         if ((rows * (int64_t)m->V + 255) / 256 > 0x7fffffffLL)
             return fail(ctx, AS_ERR_UNSUPPORTED, "logits grid too large");
