@@ -112,6 +112,11 @@ as_status as_ctx_create(as_ctx **out, int64_t max_rows, int32_t V, as_dtype logi
     c->dtype = logits_dtype;
     if (const char *shape = getenv("AS_STEP_SHAPE")) c->step_shape = atoi(shape);
     if (const char *shape = getenv("AS_GEMM_SHAPE")) c->gemm_shape = atoi(shape);
+    e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
+    if (e != hipSuccess) {
+        delete c;
+        return hip_fail(nullptr, e, "hipDeviceGetAttribute");
+    }
     e = hipMalloc(reinterpret_cast<void **>(&c->thr), (size_t)max_rows * sizeof(float));
     if (e != hipSuccess) {
         (void)hipGetLastError();

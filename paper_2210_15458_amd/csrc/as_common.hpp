@@ -53,7 +53,8 @@ struct as_ctx {
     as::DeviceBuf state;           // codes f32[rows] | prev i32[rows] | finished u8[rows]
     as::Profile prof;
     int step_shape = 0;            // work-group shape of the sampling kernel (tuning knob, 0 = default)
-    int gemm_shape = 0;            // tile shape of the logits kernel (tuning knob, 0 = default)
+    int gemm_shape = 0;            // logits kernel choice (tuning knob: 0 = persistent where it applies, 1 = tile kernel)
+    int num_cus = 0;               // compute units of the device (the persistent logits kernel runs one block on each)
     std::string err;
 };
 

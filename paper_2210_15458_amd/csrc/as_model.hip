@@ -54,12 +54,9 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *U, T *Ut, int32
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// Block tile BM x BN, K step BK; 4 waves as 2 (M) x 2 (N), each wave 64 x 128 =
-// 2 x 4 MFMA tiles of 32 x 32 (128 accumulator registers per lane).
-constexpr int BM = 128, BK = 64;
-constexpr int kPieces = BK / 8;                       // 16-byte pieces per tile row
-constexpr int kStageRows = 32;                        // C rows staged per epilogue pass
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void glb_void;
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
@@ -72,34 +69,381 @@ template <class OutT> __device__ __forceinline__ OutT to_out(float f);
 template <> __device__ __forceinline__ float to_out<float>(float f) { return f; }
 template <> __device__ __forceinline__ uint16_t to_out<uint16_t>(float f) { return f32_to_bf16_rne(f); }
 
-// Byte offset of 16-byte piece c of tile row `row`: pieces of a row are permuted
-// by the row's low bits so that 8 lanes reading the same piece index of 8
-// consecutive rows (an MFMA fragment read) touch all LDS banks once.
-#ifndef AS_GEMM_SWZ
-#define AS_GEMM_SWZ 1
-#endif
-__device__ __forceinline__ int swz(int row, int c)
+// Two fp32 values to one packed pair of bf16 (round to nearest even), low half first.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
-#if AS_GEMM_SWZ == 0
-    return row * (BK * 2) + ((c ^ (row & 7)) << 4);
-#elif AS_GEMM_SWZ == 1
-    return row * (BK * 2) + ((c ^ ((row >> 1) & 7)) << 4);
-#else
-    return row * (BK * 2 + 16) + (c << 4);
-#endif
+    uint32_t r;
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+    return r;
 }
 
-template <class OutT, int WNT, int OCC>
-__global__ __launch_bounds__(256, OCC) void bigram_gemm_bf16(const uint16_t *__restrict__ E,
+// ---- persistent kernel --------------------------------------------------------
+//
+// Block tile 256 x 256, K step 64, 512 threads = 8 waves as 4 (M) x 2 (N), each wave 64 x 128 = 2 x 4 MFMA
+// tiles of 32 x 32 (128 accumulator registers per lane).  One block per CU walks its tiles.
+//
+// Operands go global -> LDS directly (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16*l), as whole
+// 128-byte lines per tile row, into a ring of two 64 KB stages.  The load stream runs on across tile
+// boundaries: the next tile's first two stages are requested before this tile's epilogue, and because a wave's
+// vector-memory operations complete in issue order, those loads land before the epilogue's stores do.
+// Fragment reads are hand-placed ds_read_b128, one between every two MFMAs, a K slice of 16 ahead.
+// LDS rows are 128 B; 16-byte piece c of row r sits at piece c ^ ((r >> 1) & 7), which makes both the
+// 16-row fragment reads and the contiguous loader writes bank-conflict free.
+//
+// The accumulators are kept transposed (vocabulary along the MFMA's rows): register v of lane l is
+// vocabulary 8*(v/4) + 4*(l/32) + v%4 of the tile, batch row l%32, so a lane holds runs of 4 consecutive
+// logits of one row.  The epilogue stages them through a private 4 KB of LDS per wave and writes whole
+// 128-byte row pieces.
+constexpr int PM = 256, PN = 256, PK = 64;
+constexpr int kRingA = PM * PK * 2;                    // 32 KB of A rows per stage
+constexpr int kRing = (PM + PN) * PK * 2;              // 64 KB per stage
+constexpr int kWaveStage = 4096;                       // epilogue staging per wave: 32 rows x 128 B
+constexpr int kPersistLds = 2 * kRing + 8 * kWaveStage;   // 160 KB: all of a CU's LDS
+
+__device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
+{
+    bf16x8 r;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr));
+    return r;
+}
+
+template <class OutT>
+__global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t *__restrict__ E,
+                                                                 const uint16_t *__restrict__ Ut,
+                                                                 const int32_t *__restrict__ prev, int64_t R,
+                                                                 int32_t V, int32_t d, float alpha,
+                                                                 OutT *__restrict__ C, int64_t ldc, int vec_store)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[kPersistLds];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // Work-groups are handed to the 8 XCDs round-robin, so block b runs on XCD b & 7 and is worker b >> 3 of
+    // the W workers there.  XCD x owns column tiles x, x+8, ...  A worker keeps one row tile as long as it can
+    // (its gathered A rows stay the same from tile to tile) and the workers of an XCD sit on the same few
+    // column tiles at the same time, so a Ut tile is fetched into that XCD's L2 once.
+    const int64_t m_blocks = (R + PM - 1) / PM;
+    const int64_t n_blocks = ((int64_t)V + PN - 1) / PN;
+    const int W = (int)(gridDim.x >> 3);
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int64_t nbx = n_blocks > xcd ? (n_blocks - xcd + 7) / 8 : 0;
+    const int64_t cg = m_blocks < W ? W / m_blocks : 0;
+    auto item = [&](int64_t j, int64_t &bm, int64_t &bn) __attribute__((always_inline)) -> bool {
+        if (nbx <= 0) return false;
+        if (m_blocks >= W) {
+            bm = q + W * (j / nbx);
+            bn = xcd + 8 * (j % nbx);
+            return bm < m_blocks;
+        }
+        if (q >= cg * m_blocks) return false;
+        bm = q % m_blocks;
+        const int64_t bnx = q / m_blocks + cg * j;
+        bn = xcd + 8 * bnx;
+        return bnx < nbx;
+    };
+    int64_t j = 0, bm, bn, bm_next = 0, bn_next = 0;
+    if (!item(j, bm, bn)) return;
+
+    // Loader: a stage is 64 chunks of 1 KB (8 tile rows x 128 B); chunk it*8 + wave, it 0..3, is A rows
+    // it*64 + rowb, it 4..7 is B rows (it-4)*64 + rowb; a lane always moves logical piece pc of its row.
+    const uint32_t rowbytes = (uint32_t)d * 2;
+    const unsigned char *Eb = reinterpret_cast<const unsigned char *>(E);
+    const unsigned char *Ub = reinterpret_cast<const unsigned char *>(Ut);
+    const int rowb = wave * 8 + (lane >> 3);
+    const uint32_t pcoff = (uint32_t)(((lane & 7) ^ ((rowb >> 1) & 7)) << 4);
+    uint32_t aoff[4];
+    auto load_aoff = [&](int64_t m0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            int64_t m = m0 + it * 64 + rowb;
+            if (m > R - 1) m = R - 1;
+            aoff[it] = (uint32_t)prev[m] * rowbytes + pcoff;
+        }
+    };
+    // request chunk `it` of K stage `st` of the tile whose columns start at n0_ into ring slot buf_
+    auto issue1 = [&](int64_t n0_, int st, int buf_, auto it_c) __attribute__((always_inline)) {
+        constexpr int it = decltype(it_c)::value;
+        unsigned char *dst = smem + buf_ * kRing + (it * 8 + wave) * 1024;
+        if constexpr (it < 4) {
+            __builtin_amdgcn_global_load_lds((glb_void *)(Eb + (int64_t)st * (PK * 2) + aoff[it]), (lds_void *)dst,
+                                             16, 0, 0);
+        } else {
+            int64_t n = n0_ + (it - 4) * 64 + rowb;
+            if (n > V - 1) n = V - 1;
+            const uint32_t off = (uint32_t)n * rowbytes + pcoff;
+            __builtin_amdgcn_global_load_lds((glb_void *)(Ub + (int64_t)st * (PK * 2) + off), (lds_void *)dst, 16, 0,
+                                             0);
+        }
+    };
+
+    f32x16 acc[2][4];
+    const int frow = lane & 31, fc = lane >> 5;
+    uint32_t fa_addr[2], fb_addr[4];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void *)smem;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = wm * 64 + i * 32 + frow;
+        fa_addr[i] = lds_base + row * 128 + ((fc ^ ((row >> 1) & 7)) << 4);
+    }
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        const int row = wn * 128 + jj * 32 + frow;
+        fb_addr[jj] = lds_base + kRingA + row * 128 + ((fc ^ ((row >> 1) & 7)) << 4);
+    }
+
+    // The schedule below is spelled out instruction by instruction; the scheduling barriers keep it that way.
+#define AS_SB() __builtin_amdgcn_sched_barrier(0)
+#define AS_GL(n0_, st_, buf_, n_)                                                                            \
+    do {                                                                                                     \
+        issue1(n0_, st_, buf_, std::integral_constant<int, n_>{});                                           \
+        AS_SB();                                                                                             \
+    } while (0)
+    // fragment of K slice kk (0..3) of the stage at ring offset so_: the slice is an XOR on the piece index
+#define AS_RD_A(fr_, i_, so_, kk_)                                                                           \
+    do {                                                                                                     \
+        fr_[i_] = lds_read16((fa_addr[i_] + (so_)) ^ ((kk_) << 5));                                          \
+        AS_SB();                                                                                             \
+    } while (0)
+#define AS_RD_B(fr_, j_, so_, kk_)                                                                           \
+    do {                                                                                                     \
+        fr_[j_] = lds_read16((fb_addr[j_] + (so_)) ^ ((kk_) << 5));                                          \
+        AS_SB();                                                                                             \
+    } while (0)
+#define AS_MM(fa_, fb_, i_, j_)                                                                              \
+    do {                                                                                                     \
+        acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[j_], fa_[i_], acc[i_][j_], 0, 0, 0);      \
+        AS_SB();                                                                                             \
+    } while (0)
+    // the fragments are outputs of hand-written reads: tie the wait to them so no MFMA moves above it
+#define AS_WAIT_FR(fa_, fb_)                                                                                 \
+    do {                                                                                                     \
+        asm volatile("s_waitcnt lgkmcnt(0)"                                                                  \
+                     : "+v"(fa_[0]), "+v"(fa_[1]), "+v"(fb_[0]), "+v"(fb_[1]), "+v"(fb_[2]), "+v"(fb_[3]));  \
+        AS_SB();                                                                                             \
+    } while (0)
+    // multiply the slice held in (ca, cb) while reading slice kk_ into (na, nb_)
+#define AS_SLICE(ca, cb, na, nb_, so_, kk_)                                                                  \
+    do {                                                                                                     \
+        AS_RD_A(na, 0, so_, kk_); AS_MM(ca, cb, 0, 0); AS_RD_B(nb_, 0, so_, kk_); AS_MM(ca, cb, 0, 1);       \
+        AS_RD_B(nb_, 1, so_, kk_); AS_MM(ca, cb, 0, 2); AS_RD_A(na, 1, so_, kk_); AS_MM(ca, cb, 0, 3);       \
+        AS_RD_B(nb_, 2, so_, kk_); AS_MM(ca, cb, 1, 0); AS_RD_B(nb_, 3, so_, kk_); AS_MM(ca, cb, 1, 1);      \
+        AS_MM(ca, cb, 1, 2); AS_MM(ca, cb, 1, 3);                                                            \
+    } while (0)
+
+    const int nstages = d / PK;                  // host guarantees nstages >= 2
+    bf16x8 xa[2], xb[4], ya[2], yb[4];
+    int gs = 0;                                  // running stage count: stage gs lives in ring slot gs & 1
+    bool fresh = true;                           // this tile's first stages are not on their way yet
+    int stores_behind = 0;                       // stores of the previous tile issued after this tile's stage 1
+    for (;;) {
+        const int64_t m0 = bm * PM, n0 = bn * PN;
+        const bool has_next = item(j + 1, bm_next, bn_next);
+        const bool carry = has_next && bm_next == bm;      // the next tile's loads may run ahead of this epilogue
+        const int64_t n0n = bn_next * PN;
+        if (fresh) {
+            load_aoff(m0);
+            const int b0 = gs & 1, b1 = b0 ^ 1;
+            AS_GL(n0, 0, b0, 0); AS_GL(n0, 0, b0, 1); AS_GL(n0, 0, b0, 2); AS_GL(n0, 0, b0, 3);
+            AS_GL(n0, 0, b0, 4); AS_GL(n0, 0, b0, 5); AS_GL(n0, 0, b0, 6); AS_GL(n0, 0, b0, 7);
+            AS_GL(n0, 1, b1, 0); AS_GL(n0, 1, b1, 1); AS_GL(n0, 1, b1, 2); AS_GL(n0, 1, b1, 3);
+            AS_GL(n0, 1, b1, 4); AS_GL(n0, 1, b1, 5); AS_GL(n0, 1, b1, 6); AS_GL(n0, 1, b1, 7);
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");      // stage 0 has landed, stage 1 may still fly
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const uint32_t so0 = b0 * kRing;
+            AS_RD_A(xa, 0, so0, 0); AS_RD_A(xa, 1, so0, 0);
+            AS_RD_B(xb, 0, so0, 0); AS_RD_B(xb, 1, so0, 0); AS_RD_B(xb, 2, so0, 0); AS_RD_B(xb, 3, so0, 0);
+            stores_behind = 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
+        for (int s = 0; s < nstages; ++s, ++gs) {
+            const int cur = gs & 1, nb = cur ^ 1;
+            const uint32_t so = cur * kRing, son = nb * kRing;
+            // Stage s+1 (second half of its chunks, during slice 0) and stage s+2 (first half, during the last
+            // slice) are requested here; past the end of this tile they are stage 0 of the next one.  Stage 1
+            // of a tile is always requested whole before the tile starts.
+            const bool in1 = s + 1 < nstages, in2 = s + 2 < nstages;
+            const bool rd1 = in1 || carry;
+            const bool ld1 = s > 0 && (in1 || carry);
+            const bool ld2 = in2 || (carry && s + 2 == nstages);
+            const int st1 = in1 ? s + 1 : 0, st2 = in2 ? s + 2 : 0;
+            const int64_t nn1 = in1 ? n0 : n0n, nn2 = in2 ? n0 : n0n;
+            AS_WAIT_FR(xa, xb);
+            AS_RD_A(ya, 0, so, 1); AS_MM(xa, xb, 0, 0); AS_RD_B(yb, 0, so, 1); AS_MM(xa, xb, 0, 1);
+            if (ld1) AS_GL(nn1, st1, nb, 4);
+            AS_RD_B(yb, 1, so, 1); AS_MM(xa, xb, 0, 2); AS_RD_A(ya, 1, so, 1); AS_MM(xa, xb, 0, 3);
+            if (ld1) AS_GL(nn1, st1, nb, 5);
+            AS_RD_B(yb, 2, so, 1); AS_MM(xa, xb, 1, 0); AS_RD_B(yb, 3, so, 1); AS_MM(xa, xb, 1, 1);
+            if (ld1) AS_GL(nn1, st1, nb, 6);
+            AS_MM(xa, xb, 1, 2);
+            if (ld1) AS_GL(nn1, st1, nb, 7);
+            AS_MM(xa, xb, 1, 3);
+            AS_WAIT_FR(ya, yb);
+            AS_SLICE(ya, yb, xa, xb, so, 2);
+            AS_WAIT_FR(xa, xb);
+            AS_SLICE(xa, xb, ya, yb, so, 3);
+            AS_WAIT_FR(ya, yb);
+            // Every wave has read all of this stage and the next stage has landed.  Behind the next stage's
+            // loads there may be the previous tile's stores: let those drain on (vmcnt counts in issue order).
+            if (s == 0 && stores_behind == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            else if (s == 0 && stores_behind == 32) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            AS_SB();
+            if (rd1) AS_RD_A(xa, 0, son, 0);
+            AS_MM(ya, yb, 0, 0);
+            if (rd1) AS_RD_B(xb, 0, son, 0);
+            AS_MM(ya, yb, 0, 1);
+            if (ld2) AS_GL(nn2, st2, cur, 0);
+            if (rd1) AS_RD_B(xb, 1, son, 0);
+            AS_MM(ya, yb, 0, 2);
+            if (rd1) AS_RD_A(xa, 1, son, 0);
+            AS_MM(ya, yb, 0, 3);
+            if (ld2) AS_GL(nn2, st2, cur, 1);
+            if (rd1) AS_RD_B(xb, 2, son, 0);
+            AS_MM(ya, yb, 1, 0);
+            if (rd1) AS_RD_B(xb, 3, son, 0);
+            AS_MM(ya, yb, 1, 1);
+            if (ld2) AS_GL(nn2, st2, cur, 2);
+            AS_MM(ya, yb, 1, 2);
+            if (ld2) AS_GL(nn2, st2, cur, 3);
+            AS_MM(ya, yb, 1, 3);
+            if (carry && !in1) {
+                // last stage: all of the next tile's stage 1 goes into the slot this stage just left
+                AS_GL(n0n, 1, cur, 0); AS_GL(n0n, 1, cur, 1); AS_GL(n0n, 1, cur, 2); AS_GL(n0n, 1, cur, 3);
+                AS_GL(n0n, 1, cur, 4); AS_GL(n0n, 1, cur, 5); AS_GL(n0n, 1, cur, 6); AS_GL(n0n, 1, cur, 7);
+            }
+        }
+
+        // ---- epilogue: scale, round once to the storage type, transpose through this wave's 32 x 128 B of
+        // staging (16-byte pieces permuted by the row's bits 1..3), write 128-byte row pieces.  The LDS
+        // accesses are written by hand so that the compiler does not tie them to the loads in flight.
+        {
+            constexpr int kPerPiece = 16 / (int)sizeof(OutT);     // outputs per 16-byte piece
+            constexpr int kCols = 8 * kPerPiece;                  // tile columns per pass: 64 (bf16) or 32 (fp32)
+            constexpr int kPasses = 128 / kCols;                  // per 32-row group of the wave tile
+            const uint32_t stg = lds_base + 2 * kRing + wave * kWaveStage;
+            const int b = lane & 31, h = lane >> 5;
+            const bool interior = vec_store && m0 + PM <= R && n0 + PN <= V;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int ps = 0; ps < kPasses; ++ps) {
+                    if constexpr (sizeof(OutT) == 2) {
+#pragma unroll
+                        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                            for (int qq = 0; qq < 4; ++qq) {
+                                const int jx = ps * 2 + jj;
+                                u32x2 w;
+                                w[0] = pack_bf16(acc[i][jx][4 * qq + 0] * alpha, acc[i][jx][4 * qq + 1] * alpha);
+                                w[1] = pack_bf16(acc[i][jx][4 * qq + 2] * alpha, acc[i][jx][4 * qq + 3] * alpha);
+                                const int piece = (jj * 4 + qq) ^ ((b >> 1) & 7);
+                                asm volatile("ds_write_b64 %0, %1" ::"v"(stg + b * 128 + piece * 16 + h * 8), "v"(w)
+                                             : "memory");
+                            }
+                    } else {
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq) {
+                            u32x4 w;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                w[e] = __builtin_bit_cast(uint32_t, acc[i][ps][4 * qq + e] * alpha);
+                            const int piece = (qq * 2 + h) ^ ((b >> 1) & 7);
+                            asm volatile("ds_write_b128 %0, %1" ::"v"(stg + b * 128 + piece * 16), "v"(w) : "memory");
+                        }
+                    }
+                    u32x4 val[4];
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const int idx = p * 64 + lane;
+                        const int row = idx >> 3, piece = idx & 7;
+                        asm volatile("ds_read_b128 %0, %1"
+                                     : "=v"(val[p])
+                                     : "v"(stg + row * 128 + ((piece ^ ((row >> 1) & 7)) << 4))
+                                     : "memory");
+                    }
+                    asm volatile("s_waitcnt lgkmcnt(0)"
+                                 : "+v"(val[0]), "+v"(val[1]), "+v"(val[2]), "+v"(val[3])
+                                 :
+                                 : "memory");
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const int idx = p * 64 + lane;
+                        const int row = idx >> 3, piece = idx & 7;
+                        const int64_t m = m0 + wm * 64 + i * 32 + row;
+                        const int64_t n = n0 + wn * 128 + ps * kCols + piece * kPerPiece;
+                        OutT *gp = C + m * ldc + n;
+                        if (interior) {
+                            *reinterpret_cast<u32x4 *>(gp) = val[p];
+                        } else if (m < R && n < V) {
+                            if (vec_store && n + kPerPiece <= V) {
+                                *reinterpret_cast<u32x4 *>(gp) = val[p];
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < kPerPiece; ++e) {
+                                    if (n + e >= V) continue;
+                                    // (copy the lane out first: a bit cast applied to a vector element
+                                    // designator reads the vector's first element)
+                                    const uint32_t bits = val[p][sizeof(OutT) == 2 ? e >> 1 : e];
+                                    if constexpr (sizeof(OutT) == 2)
+                                        gp[e] = (OutT)(bits >> ((e & 1) * 16));
+                                    else
+                                        gp[e] = __builtin_bit_cast(OutT, bits);
+                                }
+                            }
+                        }
+                    }
+                }
+            stores_behind = interior ? 8 * kPasses : -1;
+        }
+        if (!has_next) break;
+        fresh = !carry;
+        if (fresh) {
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+        ++j;
+        bm = bm_next;
+        bn = bn_next;
+    }
+#undef AS_SB
+#undef AS_GL
+#undef AS_RD_A
+#undef AS_RD_B
+#undef AS_MM
+#undef AS_WAIT_FR
+#undef AS_SLICE
+}
+
+// ---- tile kernel: any rank d that is a multiple of 64, any size ----------------------
+//
+// Block tile 128 x 256, K step 64; 4 waves as 2 (M) x 2 (N), each wave 64 x 128.  Operands are staged
+// global -> registers -> LDS one K step ahead.  Used where the persistent kernel does not apply.
+constexpr int BM = 128, BN = 256, BK = 64;
+constexpr int kPieces = BK / 8;                       // 16-byte pieces per tile row
+constexpr int kStageRows = 32;                        // C rows staged per epilogue pass
+
+// Byte offset of 16-byte piece c of tile row `row`: pieces of a row are permuted by the row's bits 1..3 so
+// that the 16 lanes served together by a fragment read touch all LDS banks once.
+__device__ __forceinline__ int swz(int row, int c) { return row * (BK * 2) + ((c ^ ((row >> 1) & 7)) << 4); }
+
+template <class OutT>
+__global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__restrict__ E,
                                                            const uint16_t *__restrict__ Ut,
                                                            const int32_t *__restrict__ prev, int64_t R,
                                                            int32_t V, int32_t d, float alpha,
                                                            OutT *__restrict__ C, int64_t ldc, int vec_store)
 {
-    constexpr int BN = 2 * WNT * 32;                   // 2 waves along N, WNT MFMA tiles each
+    constexpr int WNT = 4;
     constexpr int kBPieces = BN / 32;                  // 16-byte pieces of B per thread and K step
-    constexpr int kRowBytes = (AS_GEMM_SWZ == 2) ? BK * 2 + 16 : BK * 2;
-    constexpr int kABytes = BM * kRowBytes, kBBytes = BN * kRowBytes;
+    constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2;
     constexpr int kStageStride = BN * (int)sizeof(OutT) + 16;          // bytes per staged C row
     constexpr int kStageBytes = kStageRows * kStageStride;
     constexpr int kLds = (kABytes + kBBytes) > kStageBytes ? (kABytes + kBBytes) : kStageBytes;
@@ -290,30 +634,32 @@ as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *pr
     const bool mfma = m->wdtype == AS_BF16 && m->d % BK == 0 &&
                       reinterpret_cast<uintptr_t>(m->E) % 16 == 0 && reinterpret_cast<uintptr_t>(m->Ut) % 16 == 0;
     if (mfma) {
-        // grid: 8 XCD lanes x ceil(column tiles / 8) x row tiles (see the kernel's tile mapping)
-        const int shape = ctx->gemm_shape;
-        const int BN = shape == 1 ? 128 : 256;
-        const int64_t m_blocks = (rows + BM - 1) / BM, n_blocks = ((int64_t)m->V + BN - 1) / BN;
-        const int64_t blocks = 8 * ((n_blocks + 7) / 8) * m_blocks;
-        if (blocks > 0x7fffffffLL) return fail(ctx, AS_ERR_UNSUPPORTED, "logits GEMM grid too large");
         const size_t osz = ctx->dtype == AS_BF16 ? 2 : 4;
         const int vec_store = (reinterpret_cast<uintptr_t>(logits_out) % 16 == 0) && ((ld * osz) % 16 == 0);
-        const dim3 grid((unsigned)blocks), block(256);
         const uint16_t *Ep = (const uint16_t *)m->E, *Up = (const uint16_t *)m->Ut;
-        if (ctx->dtype == AS_BF16) {
-            if (shape == 1)
-                launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t, 2, 4>, grid, block, 0, Ep, Up, prev, rows, m->V,
-                       m->d, alpha, (uint16_t *)logits_out, ld, vec_store);
+        // the persistent kernel addresses operand rows with 32-bit byte offsets and wants two K stages
+        const bool persistent = ctx->gemm_shape != 1 && m->d >= 2 * PK && (int64_t)m->V * m->d * 2 < (1LL << 32) &&
+                                ctx->num_cus >= 8;
+        if (persistent) {
+            const dim3 grid((unsigned)(8 * (ctx->num_cus / 8))), block(512);
+            if (ctx->dtype == AS_BF16)
+                launch(ctx, kKernelLogits, bigram_gemm_persistent<uint16_t>, grid, block, 0, Ep, Up, prev, rows,
+                       m->V, m->d, alpha, (uint16_t *)logits_out, ld, vec_store);
             else
-                launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t, 4, 2>, grid, block, 0, Ep, Up, prev, rows, m->V,
-                       m->d, alpha, (uint16_t *)logits_out, ld, vec_store);
+                launch(ctx, kKernelLogits, bigram_gemm_persistent<float>, grid, block, 0, Ep, Up, prev, rows, m->V,
+                       m->d, alpha, (float *)logits_out, ld, vec_store);
         } else {
-            if (shape == 1)
-                launch(ctx, kKernelLogits, bigram_gemm_bf16<float, 2, 4>, grid, block, 0, Ep, Up, prev, rows, m->V,
-                       m->d, alpha, (float *)logits_out, ld, vec_store);
+            // grid: 8 XCD lanes x ceil(column tiles / 8) x row tiles (see the kernel's tile mapping)
+            const int64_t m_blocks = (rows + BM - 1) / BM, n_blocks = ((int64_t)m->V + BN - 1) / BN;
+            const int64_t blocks = 8 * ((n_blocks + 7) / 8) * m_blocks;
+            if (blocks > 0x7fffffffLL) return fail(ctx, AS_ERR_UNSUPPORTED, "logits GEMM grid too large");
+            const dim3 grid((unsigned)blocks), block(256);
+            if (ctx->dtype == AS_BF16)
+                launch(ctx, kKernelLogits, bigram_gemm_bf16<uint16_t>, grid, block, 0, Ep, Up, prev, rows, m->V,
+                       m->d, alpha, (uint16_t *)logits_out, ld, vec_store);
             else
-                launch(ctx, kKernelLogits, bigram_gemm_bf16<float, 4, 2>, grid, block, 0, Ep, Up, prev, rows, m->V,
-                       m->d, alpha, (float *)logits_out, ld, vec_store);
+                launch(ctx, kKernelLogits, bigram_gemm_bf16<float>, grid, block, 0, Ep, Up, prev, rows, m->V, m->d,
+                       alpha, (float *)logits_out, ld, vec_store);
         }
     } else {
         if ((rows * (int64_t)m->V + 255) / 256 > 0x7fffffffLL)
