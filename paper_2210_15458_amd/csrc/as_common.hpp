@@ -54,6 +54,7 @@ struct as_ctx {
     as::Profile prof;
     int step_shape = 0;            // work-group shape of the sampling kernel (tuning knob, 0 = default)
     int gemm_shape = 0;            // logits kernel choice (tuning knob: 0 = persistent where it applies, 1 = tile kernel)
+    int thr_path = 0;              // keep-threshold kernel choice (tuning knob: 0 = resident where it applies, 1 = radix)
     int num_cus = 0;               // compute units of the device (the persistent logits kernel runs one block on each)
     std::string err;
 };

@@ -12,6 +12,17 @@
 //            The group of equal logits that closes the nucleus stays whole.
 // Mass is accumulated in fixed point (integer atomics) so that the result does
 // not depend on the order in which lanes reach the histogram.
+//
+// The radix select reads the row once per digit and its histograms are hot in a
+// few bins (the leading digit of a bell-shaped row is mostly sign and exponent),
+// so it is the general path only.  Rows of up to 32768 logits that can be read in
+// 16-byte pieces take the resident path further down: the row is loaded once into
+// registers, a coarse histogram with evenly filled bins finds the neighbourhood of
+// the answer, and the few logits in that neighbourhood are ranked exactly.  Both
+// paths use the same keys and the same fixed-point masses, so they return the
+// same threshold.
+#include <type_traits>
+
 #include "as_common.hpp"
 
 namespace as {
@@ -52,6 +63,13 @@ template <> struct Key<AS_F32> {
     }
 };
 
+// Probability mass of a logit in fixed point: 31 fractional bits relative to 2^ceil(max*k), nr = -ceil(max*k).
+__device__ __forceinline__ unsigned long long mass_q(float x, float k, float nr)
+{
+    const float e = __builtin_amdgcn_exp2f(fmaf(x, k, nr));
+    return (unsigned long long)(uint32_t)(e * 2147483648.f + 0.5f);
+}
+
 struct Shared {
     unsigned long long hist[kMaxBins];
     unsigned long long part[kThreads];
@@ -63,7 +81,7 @@ struct Shared {
 };
 
 // Exclusive prefix of one value per thread, thread order, plus the block total.
-__device__ __forceinline__ unsigned long long block_excl_scan(unsigned long long x, Shared &sh,
+__device__ __forceinline__ unsigned long long block_excl_scan(unsigned long long x, unsigned long long *wave_tot,
                                                               unsigned long long &total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -73,12 +91,12 @@ __device__ __forceinline__ unsigned long long block_excl_scan(unsigned long long
         const unsigned long long y = __shfl_up(incl, d, 64);
         if (lane >= d) incl += y;
     }
-    if (lane == 63) sh.wave_tot[wave] = incl;
+    if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
     unsigned long long base = 0, tot = 0;
 #pragma unroll
     for (int w = 0; w < kThreads / 64; ++w) {
-        const unsigned long long t = sh.wave_tot[w];
+        const unsigned long long t = wave_tot[w];
         if (w < wave) base += t;
         tot += t;
     }
@@ -102,7 +120,7 @@ __device__ __forceinline__ void pick_digit(Shared &sh, int nb, unsigned long lon
     }
     if (threadIdx.x == 0) sh.digit = -1;
     unsigned long long total;
-    const unsigned long long excl = block_excl_scan(local, sh, total);
+    const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
     // exactly one thread sees the predicate flip inside its bins
     if (!reached(before + excl) && reached(before + excl + local)) {
         unsigned long long acc = before + excl;
@@ -133,21 +151,13 @@ __device__ __forceinline__ void pick_digit(Shared &sh, int nb, unsigned long lon
     }
 }
 
+// Radix select over one row; every thread of the block returns the threshold key.
 template <int DT>
-__global__ __launch_bounds__(kThreads) void threshold_kernel(const void *logits, int64_t ld, int32_t V,
-                                                             const uint8_t *finished_in,
-                                                             const int32_t *row_ids, float temp,
-                                                             int32_t top_k, float top_p, float *thr_out)
+__device__ __forceinline__ uint32_t radix_threshold(Shared &sh, const typename Key<DT>::T *row, int32_t V, float temp,
+                                                    int32_t top_k, float top_p)
 {
     using K = Key<DT>;
     using T = typename K::T;
-    __shared__ Shared sh;
-
-    const int64_t r = blockIdx.x;
-    if (finished_in != nullptr && finished_in[r] != 0) return;
-    const int64_t src = row_ids ? (int64_t)row_ids[r] : r;
-    const T *row = reinterpret_cast<const T *>(logits) + src * ld;
-
     uint32_t thr_key = 0;               // keep key >= thr_key
 
     // ---------------- top-k: k-th largest key, counted with multiplicity
@@ -203,9 +213,7 @@ __global__ __launch_bounds__(kThreads) void threshold_kernel(const void *logits,
                 const T h = row[v];
                 const uint32_t key = K::key(h);
                 if (key >= thr_key && (done == 0 || (key >> (shift + w)) == prefix)) {
-                    // fixed point, 31 fractional bits relative to 2^ceil(max*k)
-                    const float e = __builtin_amdgcn_exp2f(fmaf(K::value(h), k, nr));
-                    const unsigned long long q = (unsigned long long)(uint32_t)(e * 2147483648.f + 0.5f);
+                    const unsigned long long q = mass_q(K::value(h), k, nr);
                     if (q) atomicAdd(&sh.hist[(key >> shift) & (uint32_t)(nb - 1)], q);
                 }
             }
@@ -214,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void threshold_kernel(const void *logits,
                 // total mass = sum of the first histogram
                 unsigned long long local = 0, total;
                 for (int b = threadIdx.x; b < nb; b += kThreads) local += sh.hist[b];
-                block_excl_scan(local, sh, total);
+                block_excl_scan(local, sh.wave_tot, total);
                 need = (double)top_p * (double)total;
             }
             pick_digit(sh, nb, before, [&](unsigned long long c) { return (double)c >= need; });
@@ -225,23 +233,469 @@ __global__ __launch_bounds__(kThreads) void threshold_kernel(const void *logits,
         }
         if (prefix > thr_key) thr_key = prefix;
     }
+    return thr_key;
+}
 
+template <int DT>
+__global__ __launch_bounds__(kThreads) void threshold_kernel(const void *logits, int64_t ld, int32_t V,
+                                                             const uint8_t *finished_in,
+                                                             const int32_t *row_ids, float temp,
+                                                             int32_t top_k, float top_p, float *thr_out)
+{
+    using K = Key<DT>;
+    using T = typename K::T;
+    __shared__ Shared sh;
+    const int64_t r = blockIdx.x;
+    if (finished_in != nullptr && finished_in[r] != 0) return;
+    const int64_t src = row_ids ? (int64_t)row_ids[r] : r;
+    const T *row = reinterpret_cast<const T *>(logits) + src * ld;
+    const uint32_t thr_key = radix_threshold<DT>(sh, row, V, temp, top_k, top_p);
     if (threadIdx.x == 0) thr_out[r] = K::from_key(thr_key);
 }
 
+// ------------------------------------------------------------ resident path
+
+constexpr int kCoarseBins = 2048;        // mass histogram: 64 bins per factor of two below the row's reference
+constexpr int kCandCap = 1024;           // logits ranked exactly
+
+struct Resident {
+    unsigned long long hist[kCoarseBins];
+    uint32_t ckey[kCandCap];
+    uint32_t cq[kCandCap];
+    uint32_t mcount[kThreads];           // thread maxima per coarse bin (top-k)
+    unsigned long long wave_tot[kThreads / 64];
+    uint32_t ncand;
+    uint32_t pick;                       // coarse bin / key handed from the thread that found it
+    uint32_t lkey;
+    int fallback;
+};
+
+union Scratch {
+    Shared radix;
+    Resident res;
+};
+
+__device__ __forceinline__ uint32_t wave_reduce_umax(uint32_t x)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t y = (uint32_t)__shfl_xor((int)x, d, 64);
+        x = x > y ? x : y;
+    }
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_reduce_umin(uint32_t x)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t y = (uint32_t)__shfl_xor((int)x, d, 64);
+        x = x < y ? x : y;
+    }
+    return x;
+}
+
+// Coarse bin of a logit whose exponent argument (base 2, relative to the row's reference) is y <= 0.
+__device__ __forceinline__ int coarse_bin(float y)
+{
+    const float b = fminf(fmaxf(-y * 64.f, 0.f), (float)(kCoarseBins - 1));
+    return (int)b;
+}
+
+template <int DT, bool HAS_K, bool HAS_P>
+__global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void *logits, int64_t ld, int32_t V,
+                                                                      const uint8_t *finished_in,
+                                                                      const int32_t *row_ids, float temp,
+                                                                      int32_t top_k, float top_p, float *thr_out)
+{
+    using K = Key<DT>;
+    using T = typename K::T;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr bool kHalf = sizeof(T) == 2;               // two logits per register
+    constexpr int EPP = 16 / (int)sizeof(T);             // logits per 16-byte piece
+    constexpr int NP = 32768 / (EPP * kThreads);         // pieces per thread: 16 (bf16) or 32 (fp32)
+    __shared__ Scratch sc;
+    Resident &sh = sc.res;
+
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    if (finished_in != nullptr && finished_in[r] != 0) return;
+    const int64_t src = row_ids ? (int64_t)row_ids[r] : r;
+    const T *row = reinterpret_cast<const T *>(logits) + src * ld;
+
+    // The row, resident: piece p of this thread holds logits (p*256 + tid)*EPP ... + EPP-1.  With top-k the
+    // registers hold the order-preserving keys (0 = "no logit here", below every real key), otherwise the
+    // stored values with the positions past V set to -inf.
+    u32x4 pc[NP];
+    const int32_t npieces = (V + EPP - 1) / EPP;
+    constexpr uint32_t kNegInf = kHalf ? 0xff80ff80u : 0xff800000u;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int32_t piece = p * kThreads + tid;
+        if (piece < npieces) pc[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + piece);
+        else pc[p] = u32x4{kNegInf, kNegInf, kNegInf, kNegInf};
+    }
+    if (V % EPP != 0) {
+        // the one piece that straddles V
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int32_t piece = p * kThreads + tid;
+            if (piece == npieces - 1) {
+                const int live = V - piece * EPP;            // 1 .. EPP-1
+#pragma unroll
+                for (int e = 0; e < EPP; ++e) {
+                    if (e < live) continue;
+                    if constexpr (kHalf) pc[p][e >> 1] = (e & 1) ? ((pc[p][e >> 1] & 0xffffu) | 0xff800000u)
+                                                                  : ((pc[p][e >> 1] & 0xffff0000u) | 0xff80u);
+                    else pc[p][e] = kNegInf;
+                }
+            }
+        }
+    }
+    if (HAS_K) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const bool live = p * kThreads + tid < npieces;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t w = pc[p][i];
+                if constexpr (kHalf) {
+                    const uint32_t neg = ((w >> 15) & 0x00010001u) * 0xffffu;     // 0xffff in each negative half
+                    w ^= neg | 0x80008000u;
+                } else {
+                    w ^= (uint32_t)((int32_t)w >> 31) | 0x80000000u;
+                }
+                pc[p][i] = live ? w : 0u;
+            }
+        }
+        if (V % EPP != 0) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int32_t piece = p * kThreads + tid;
+                if (piece == npieces - 1) {
+                    const int live = V - piece * EPP;
+#pragma unroll
+                    for (int e = 0; e < EPP; ++e) {
+                        if (e < live) continue;
+                        if constexpr (kHalf) pc[p][e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                        else pc[p][e] = 0u;
+                    }
+                }
+            }
+        }
+    }
+
+    // Between passes over the resident row: make the compiler forget what it derived from the registers, or
+    // it keeps every unpacked value of one pass alive for the next and the kernel no longer fits.
+    auto forget_row = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) asm volatile("" : "+v"(pc[p]));
+    };
+
+    uint32_t thr_key = 0;
+    bool fall = false;
+    uint32_t ncand = 0;
+
+    // ---------------- top-k.  The k-th largest of the 256 thread maxima bounds the k-th largest logit from
+    // below, and for anything but adversarial rows only a few more than k logits reach it.
+    if (HAS_K) {
+        uint32_t tmax;
+        if constexpr (kHalf) {
+            uint32_t mh = 0, ml = 0;
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = pc[p][i];
+                    mh = w > mh ? w : mh;
+                    const uint32_t l = w << 16;
+                    ml = l > ml ? l : ml;
+                }
+            mh >>= 16; ml >>= 16;
+            tmax = mh > ml ? mh : ml;
+        } else {
+            tmax = 0;
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tmax = pc[p][i] > tmax ? pc[p][i] : tmax;
+        }
+        sh.mcount[tid] = 0;
+        if (tid == 0) sh.ncand = 0;
+        // range of the maxima -> 256 even bins over it, bin 0 the highest
+        uint32_t hi = wave_reduce_umax(tmax), lo = wave_reduce_umin(tmax);
+        uint32_t *red = reinterpret_cast<uint32_t *>(sh.hist);
+        if ((tid & 63) == 0) { red[tid >> 6] = hi; red[4 + (tid >> 6)] = lo; }
+        __syncthreads();
+        hi = red[0]; lo = red[4];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) { hi = red[w] > hi ? red[w] : hi; lo = red[4 + w] < lo ? red[4 + w] : lo; }
+        const float scale = 256.f / ((float)(hi - lo) + 1.f);
+        int mb = (int)((float)(hi - tmax) * scale);
+        mb = mb > kThreads - 1 ? kThreads - 1 : mb;
+        atomicAdd(&sh.mcount[mb], 1u);
+        __syncthreads();
+        // first bin (from the top) at which k maxima have been seen
+        unsigned long long total;
+        const unsigned long long mine = sh.mcount[tid];
+        const unsigned long long excl = block_excl_scan(mine, sh.wave_tot, total);
+        if (excl < (unsigned long long)top_k && excl + mine >= (unsigned long long)top_k) sh.pick = (uint32_t)tid;
+        if (tid == 0) sh.lkey = 0xffffffffu;
+        __syncthreads();
+        // the lowest maximum in the bins up to there
+        uint32_t l = mb <= (int)sh.pick ? tmax : 0xffffffffu;
+        l = wave_reduce_umin(l);
+        if ((tid & 63) == 0) atomicMin(&sh.lkey, l);
+        __syncthreads();
+        const uint32_t lkey = sh.lkey;
+        forget_row();
+        auto candidate = [&](uint32_t key) __attribute__((always_inline)) {
+            const uint32_t i = atomicAdd(&sh.ncand, 1u);
+            if (i < (uint32_t)kCandCap) sh.ckey[i] = key;
+        };
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t w = pc[p][i];
+                if constexpr (kHalf) {
+                    const uint32_t t = lkey << 16;
+                    if (w >= t || (w << 16) >= t) {          // rare
+                        if ((w >> 16) >= lkey) candidate(w >> 16);
+                        if ((w & 0xffffu) >= lkey) candidate(w & 0xffffu);
+                    }
+                } else {
+                    if (w >= lkey) candidate(w);
+                }
+            }
+        __syncthreads();
+        ncand = sh.ncand;
+        if (ncand > (uint32_t)kCandCap) {
+            fall = true;
+        } else {
+            // rank the candidates: the one with exactly k-1 ahead of it is the k-th largest logit
+            for (uint32_t c = tid; c < ncand; c += kThreads) {
+                const uint32_t my = sh.ckey[c];
+                uint32_t ahead = 0;
+                for (uint32_t j = 0; j < ncand; ++j) {
+                    const uint32_t o = sh.ckey[j];
+                    ahead += (o > my || (o == my && j < c)) ? 1u : 0u;
+                }
+                if (ahead == (uint32_t)top_k - 1u) sh.pick = my;
+            }
+            __syncthreads();
+            thr_key = sh.pick;
+        }
+        __syncthreads();
+    }
+
+    // ---------------- nucleus over the survivors
+    if (HAS_P && !fall) {
+        const float k = 1.44269504088896340736f / temp;
+        double need;
+        unsigned long long before = 0;
+        if (HAS_K) {
+            // every survivor of top-k is in the candidate table: work on that
+            float m = -__builtin_inff();
+            for (uint32_t c = tid; c < ncand; c += kThreads)
+                if (sh.ckey[c] >= thr_key) m = fmaxf(m, K::from_key(sh.ckey[c]));
+            m = wave_max(m);
+            float *fred = reinterpret_cast<float *>(sh.hist);
+            if ((tid & 63) == 0) fred[tid >> 6] = m;
+            __syncthreads();
+            m = fred[0];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
+            const float nr = -fmaxf(ceilf(m * k), -100000.f);
+            unsigned long long local = 0, total;
+            for (uint32_t c = tid; c < ncand; c += kThreads) {
+                const uint32_t key = sh.ckey[c];
+                const unsigned long long q = key >= thr_key ? mass_q(K::from_key(key), k, nr) : 0ull;
+                sh.cq[c] = (uint32_t)q;                 // 0 also takes the candidates below the threshold out
+                local += q;
+            }
+            block_excl_scan(local, sh.wave_tot, total);
+            need = (double)top_p * (double)total;
+            __syncthreads();
+        } else {
+            float m = -__builtin_inff();
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = pc[p][i];
+                    if constexpr (kHalf) {
+                        m = fmaxf(m, __builtin_bit_cast(float, w << 16));
+                        m = fmaxf(m, __builtin_bit_cast(float, w & 0xffff0000u));
+                    } else {
+                        m = fmaxf(m, __builtin_bit_cast(float, w));
+                    }
+                }
+            m = wave_max(m);
+            float *fred = reinterpret_cast<float *>(sh.ckey);
+            if ((tid & 63) == 0) fred[tid >> 6] = m;
+            for (int b = tid; b < kCoarseBins; b += kThreads) sh.hist[b] = 0;
+            if (tid == 0) sh.ncand = 0;
+            __syncthreads();
+            m = fred[0];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
+            const float nr = -fmaxf(ceilf(m * k), -100000.f);
+            __syncthreads();
+            // mass per coarse bin, in the fixed point of the radix path
+            forget_row();
+            auto add_mass = [&](float x) __attribute__((always_inline)) {
+                const float y = fmaf(x, k, nr);
+                const float e = __builtin_amdgcn_exp2f(y);
+                const uint32_t q = (uint32_t)(e * 2147483648.f + 0.5f);
+                if (q) atomicAdd(&sh.hist[coarse_bin(y)], (unsigned long long)q);
+            };
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = pc[p][i];
+                    if constexpr (kHalf) {
+                        add_mass(__builtin_bit_cast(float, w << 16));
+                        add_mass(__builtin_bit_cast(float, w & 0xffff0000u));
+                    } else {
+                        add_mass(__builtin_bit_cast(float, w));
+                    }
+                }
+            __syncthreads();
+            // total, then the first bin (from the top) at which top_p of it is reached
+            constexpr int kPer = kCoarseBins / kThreads;
+            unsigned long long local = 0, total;
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) local += sh.hist[tid * kPer + i];
+            const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
+            need = (double)top_p * (double)total;
+            if (!((double)excl >= need) && (double)(excl + local) >= need) {
+                unsigned long long acc = excl;
+                for (int i = 0; i < kPer; ++i) {
+                    const unsigned long long h = sh.hist[tid * kPer + i];
+                    if ((double)(acc + h) >= need) {
+                        sh.pick = (uint32_t)(tid * kPer + i);
+                        // mass above the bin, split over two words of the (still free) candidate key table
+                        sh.ckey[kCandCap - 2] = (uint32_t)acc;
+                        sh.ckey[kCandCap - 1] = (uint32_t)(acc >> 32);
+                        break;
+                    }
+                    acc += h;
+                }
+            }
+            __syncthreads();
+            const float pickf = (float)sh.pick;
+            before = (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
+            __syncthreads();
+            // the logits of that bin go to the candidate table
+            // (second pass over the row: keep the compiler from holding every exponent of the first pass in a
+            // register until here)
+            float nr2 = nr;
+            asm volatile("" : "+v"(nr2));
+            forget_row();
+            auto maybe_candidate = [&](uint32_t bits) __attribute__((always_inline)) {
+                const float x = __builtin_bit_cast(float, bits);
+                const float y = fmaf(x, k, nr2);
+                const float t = fminf(fmaxf(-y * 64.f, 0.f), (float)(kCoarseBins - 1));   // as in coarse_bin
+                if (t >= pickf && t < pickf + 1.f) {
+                    const unsigned long long q = mass_q(x, k, nr2);
+                    if (q) {
+                        const uint32_t i = atomicAdd(&sh.ncand, 1u);
+                        if (i < (uint32_t)kCandCap) {
+                            sh.ckey[i] = kHalf ? K::key((T)(bits >> 16)) : K::key(__builtin_bit_cast(T, (typename std::conditional<kHalf, uint16_t, uint32_t>::type)bits));
+                            sh.cq[i] = (uint32_t)q;
+                        }
+                    }
+                }
+            };
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = pc[p][i];
+                    if constexpr (kHalf) {
+                        maybe_candidate(w << 16);
+                        maybe_candidate(w & 0xffff0000u);
+                    } else {
+                        maybe_candidate(w);
+                    }
+                }
+            __syncthreads();
+            ncand = sh.ncand;
+            if (ncand > (uint32_t)kCandCap) fall = true;
+        }
+        if (!fall) {
+            // rank exactly: the nucleus closes with a whole group of equal logits
+            for (uint32_t c = tid; c < ncand; c += kThreads) {
+                const uint32_t my = sh.ckey[c];
+                if (sh.cq[c] == 0) continue;
+                unsigned long long above = before, group = 0;
+                for (uint32_t j = 0; j < ncand; ++j) {
+                    const uint32_t o = sh.ckey[j];
+                    const unsigned long long q = sh.cq[j];
+                    above += o > my ? q : 0ull;
+                    group += o == my ? q : 0ull;
+                }
+                if (!((double)above >= need) && (double)(above + group) >= need) sh.pick = my;
+            }
+            __syncthreads();
+            const uint32_t pkey = sh.pick;
+            if (pkey > thr_key) thr_key = pkey;
+        }
+    }
+
+    if (fall) {            // uniform over the block: every thread saw the same counters
+        __syncthreads();
+        thr_key = radix_threshold<DT>(sc.radix, row, V, temp, top_k, top_p);
+    }
+    if (tid == 0) thr_out[r] = K::from_key(thr_key);
+}
+
 }  // namespace
+
+template <int DT>
+void launch_resident(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, const uint8_t *finished_in,
+                     const int32_t *row_ids, float temp, int32_t top_k, float top_p, float *thr_out, bool has_k,
+                     bool has_p)
+{
+    const dim3 grid((unsigned)rows), block(kThreads);
+    if (has_k && has_p)
+        launch(ctx, kKernelThreshold, threshold_resident_kernel<DT, true, true>, grid, block, 0, logits, ld, ctx->V,
+               finished_in, row_ids, temp, top_k, top_p, thr_out);
+    else if (has_k)
+        launch(ctx, kKernelThreshold, threshold_resident_kernel<DT, true, false>, grid, block, 0, logits, ld, ctx->V,
+               finished_in, row_ids, temp, top_k, top_p, thr_out);
+    else
+        launch(ctx, kKernelThreshold, threshold_resident_kernel<DT, false, true>, grid, block, 0, logits, ld, ctx->V,
+               finished_in, row_ids, temp, top_k, top_p, thr_out);
+}
 
 as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
                            const uint8_t *finished_in, const int32_t *row_ids, float temp,
                            int32_t top_k, float top_p, float *thr_out)
 {
     if (rows == 0) return AS_OK;
-    if (ctx->dtype == AS_BF16)
+    const size_t esz = ctx->dtype == AS_BF16 ? 2 : 4;
+    const bool has_k = top_k > 0 && top_k < ctx->V, has_p = top_p > 0.f && top_p < 1.f;
+    // resident path: the row fits the block's registers, is read in 16-byte pieces, k at most half the thread
+    // count (the k-th largest thread maximum must leave only a few hundred logits above it)
+    const bool resident = ctx->thr_path != 1 && (has_k || has_p) && ctx->V <= 32768 &&
+                          reinterpret_cast<uintptr_t>(logits) % 16 == 0 && (ld * esz) % 16 == 0 &&
+                          (!has_k || top_k <= kThreads / 2);
+    if (resident) {
+        if (ctx->dtype == AS_BF16)
+            launch_resident<AS_BF16>(ctx, logits, rows, ld, finished_in, row_ids, temp, top_k, top_p, thr_out, has_k,
+                                     has_p);
+        else
+            launch_resident<AS_F32>(ctx, logits, rows, ld, finished_in, row_ids, temp, top_k, top_p, thr_out, has_k,
+                                    has_p);
+    } else if (ctx->dtype == AS_BF16) {
         launch(ctx, kKernelThreshold, threshold_kernel<AS_BF16>, dim3((unsigned)rows), dim3(kThreads), 0,
                logits, ld, ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);
-    else
+    } else {
         launch(ctx, kKernelThreshold, threshold_kernel<AS_F32>, dim3((unsigned)rows), dim3(kThreads), 0,
                logits, ld, ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);
+    }
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }

@@ -114,6 +114,41 @@ def test_step_truncation(dtype, top_k, top_p, temp):
     _check(1001, 40, dtype, temp=temp, top_k=min(top_k, 900), top_p=top_p, seed=32)
 
 
+@pytest.mark.parametrize("top_k,top_p", [(40, 1.0), (0, 0.9), (5, 0.5)])
+def test_step_truncation_radix_path(top_k, top_p, monkeypatch):
+    # the general keep-threshold kernel on rows that would otherwise take the resident one
+    monkeypatch.setenv("AS_THR_PATH", "1")
+    _check(32128, 48, "bf16", top_k=top_k, top_p=top_p, seed=35)
+    _check(32128, 24, "f32", top_k=top_k, top_p=top_p, seed=36)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_truncation_hard_rows(dtype):
+    """Rows on which the resident keep-threshold kernel has to hand over to the radix select, and the edges of
+    what it takes."""
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    V, R = 32128, 12
+    rng = np.random.default_rng(77)
+    x = rng.normal(0.0, 3.0, (R, V)).astype(np.float32)
+    x[0, :] = 1.25                                   # every logit equal: all tie at the k-th place
+    x[1, :] = np.round(x[1, :])                      # heavy ties (a few dozen distinct values)
+    x[2, :] *= 0.001                                 # flat: the nucleus is 90 % of the vocabulary
+    x[3, 100:] = -np.inf                             # only 100 live tokens
+    x[4, ::2] = -np.inf                              # every other token masked out
+    x[5, :] = -30.0; x[5, 17] = 5.0                  # one-hot
+    x[6, :5000] += 40.0                              # 5000 tokens far above the rest
+    x[7, :] = np.where(rng.random(V) < 0.5, 2.0, -2.0)   # two values
+    stored = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    codes = synth.uniform_codes(R, seed=78)
+    for top_k, top_p, temp in [(40, 1.0, 1.0), (256, 1.0, 1.0), (257, 1.0, 1.0), (0, 0.9, 1.0), (0, 0.5, 0.7),
+                               (100, 0.9, 1.0), (0, 0.999, 2.0)]:
+        label = f"hard rows {dtype} k={top_k} p={top_p} temp={temp}"
+        print("case", label, flush=True)
+        gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p)
+        ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p)
+        print("   ", compare_step(gpu, ref, V, label, trunc=True), flush=True)
+
+
 def test_step_truncation_multi_tile():
     _check(256000, 6, "bf16", top_k=40, seed=33)
     _check(256000, 6, "bf16", top_p=0.9, seed=34)
