@@ -50,6 +50,11 @@ def lib():
             C.c_int, C.c_int32, C.c_void_p, C.c_int32, C.c_double, C.c_int32,
             C.c_double, C.c_int32, C.c_void_p, C.c_void_p]
         L.ao_encode.restype = C.c_int
+        L.ao_token_interval_rows.argtypes = [
+            C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int32, C.c_void_p,
+            C.c_void_p, C.c_double, C.c_int32, C.c_double, C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_int]
+        L.ao_token_interval_rows.restype = C.c_int
         L.ao_max_threads.argtypes = []
         L.ao_max_threads.restype = C.c_int
         _lib = L
@@ -158,6 +163,32 @@ def decode(E, U, prompts, N, T, codes0, temp=1.0, top_k=0, top_p=1.0,
         out["p"] = p.reshape(B, N, T)
         out["delta"] = dl.reshape(B, N, T)
     return out
+
+
+def token_interval(stored, tokens, temp=1.0, top_k=0, top_p=1.0, V=None,
+                   finished=None, row_ids=None, nthreads=1):
+    """Per row: (f_lo, p) of tokens[r] in the row's kept, tempered softmax.
+
+    `stored` as in `step`.  One step of the codebook recursion for a known
+    next token; finished rows give (0, 1).
+    """
+    stored, dt = _stored(stored)
+    rows_avail, ld = stored.shape
+    V = ld if V is None else int(V)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    rows = tokens.shape[0]
+    rid = None if row_ids is None else np.ascontiguousarray(row_ids, dtype=np.int64)
+    fin = None if finished is None else np.ascontiguousarray(finished, dtype=np.uint8)
+    f_lo = np.empty(rows, dtype=np.float64)
+    p = np.empty(rows, dtype=np.float64)
+    rc = lib().ao_token_interval_rows(_ptr(stored), dt, rows, ld, V,
+                                      _ptr(rid), _ptr(tokens),
+                                      float(temp), int(top_k), float(top_p),
+                                      _ptr(fin),
+                                      _ptr(f_lo), _ptr(p), int(nthreads))
+    if rc != 0:
+        raise MemoryError("oracle token_interval failed")
+    return f_lo, p
 
 
 def encode(E, U, prompt, seq, temp=1.0, top_k=0, top_p=1.0, eos_id=-1,

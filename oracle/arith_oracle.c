@@ -442,6 +442,73 @@ int ao_decode(const void *E, const void *U, int wdtype, int32_t V, int32_t d,
 /* ------------------------------------------------------------------ */
 
 /*
+ * One step of the codebook recursion of Sec. 4.1 for a given next token:
+ * within the current prefix's interval the token's sub-interval starts at
+ * the cumulative probability of the tokens before it in vocabulary order
+ * and has the token's conditional probability as its width (Sec. 3.1).
+ * x holds the row's logits; e, s are scratch of V doubles.
+ */
+static void token_interval(const double *x, int32_t V, double temp,
+                           int32_t top_k, double top_p, int32_t token,
+                           double *e, double *s, double *f_lo, double *p)
+{
+    int32_t n_kept; double nm;
+    double S = kept_weights(x, V, temp, top_k, top_p, e, s, &n_kept, &nm);
+    double before = 0.0;
+    for (int32_t v = 0; v < token; ++v) before += e[v];
+    *f_lo = before / S;
+    *p = e[token] / S;
+}
+
+/*
+ * token_interval over rows of stored logits (layout and dtype as in
+ * ao_step_rows): f_lo[r], p[r] for tokens[r].  Finished rows (already past
+ * their EOS, Sec. 3.3) do not narrow the interval: f_lo = 0, p = 1.
+ * Returns 0, -1 on allocation failure.
+ */
+int ao_token_interval_rows(const void *logits, int dtype, int64_t rows,
+                           int64_t ld, int32_t V, const int64_t *row_ids,
+                           const int32_t *tokens, double temp, int32_t top_k,
+                           double top_p, const uint8_t *finished_in,
+                           double *f_lo, double *p, int nthreads)
+{
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel num_threads(nthreads)
+#endif
+    {
+        double *x = (double *)malloc((size_t)V * sizeof(double));
+        double *e = (double *)malloc((size_t)V * sizeof(double));
+        double *s = (double *)malloc((size_t)V * sizeof(double));
+        if (!x || !e || !s) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp barrier
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t r = 0; r < rows; ++r) {
+            if (failed) continue;
+            if (finished_in && finished_in[r]) {
+                f_lo[r] = 0.0; p[r] = 1.0;
+                continue;
+            }
+            int64_t src = row_ids ? row_ids[r] : r;
+            for (int32_t v = 0; v < V; ++v)
+                x[v] = load_elem(logits, dtype, src * ld + v);
+            token_interval(x, V, temp, top_k, top_p, tokens[r], e, s,
+                           &f_lo[r], &p[r]);
+        }
+        free(x); free(e); free(s);
+    }
+    return failed ? -1 : 0;
+}
+
+/*
  * Interval [w, w + P) of the prefix seq[0..L) under the same model and logit
  * modifiers: w grows by P(prefix so far) times the cumulative probability of
  * the tokens ordered before the next one; P(prefix) is multiplied by that
@@ -462,12 +529,10 @@ int ao_encode(const void *E, const void *U, int wdtype, int32_t V, int32_t d,
     int32_t prev = prompt;
     for (int32_t t = 0; t < L; ++t) {
         ao_bigram_logits(E, U, wdtype, V, d, scale, prev, round_mode, x);
-        int32_t n_kept; double nm;
-        double S = kept_weights(x, V, temp, top_k, top_p, e, s, &n_kept, &nm);
-        double before = 0.0;
-        for (int32_t v = 0; v < seq[t]; ++v) before += e[v];
-        w += P * (before / S);
-        P *= e[seq[t]] / S;
+        double f_lo, p;
+        token_interval(x, V, temp, top_k, top_p, seq[t], e, s, &f_lo, &p);
+        w += P * f_lo;
+        P *= p;
         prev = seq[t];
         if (eos_id >= 0 && seq[t] == eos_id) break;
     }

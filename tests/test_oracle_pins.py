@@ -294,6 +294,64 @@ def test_monotone_in_code():
 # --------------------------------------------------------------------------
 # P9  one step with a fresh uniform is inverse-CDF categorical sampling
 #     (Sec. 3.1, last paragraph): NumPy cumsum + searchsorted
+
+# --------------------------------------------------------------------------
+# P9b. the interval of a known next token (one step of the codebook recursion,
+#      Sec. 4.1): NumPy cumsum restatement, the rule "codes in [f_lo, f_lo+p)
+#      decode to that token" (Sec. 3.1), and the chain of steps against the
+#      sequence interval pinned above by enumeration
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("temp,top_k,top_p", [(1.0, 0, 1.0), (0.7, 0, 1.0), (1.0, 9, 1.0), (1.3, 0, 0.8)])
+def test_token_interval_is_cumsum_before_token(dtype, temp, top_k, top_p):
+    rng = np.random.default_rng(41)
+    R, V = 120, 157
+    x = (rng.standard_normal((R, V)) * 3).astype(np.float32)
+    if dtype == "bf16":
+        stored = synth.f32_to_bf16_bits(x)
+        wide = synth.bf16_bits_to_f32(stored).astype(np.float64)
+    else:
+        stored, wide = x, x.astype(np.float64)
+    tokens = rng.integers(0, V, R).astype(np.int32)
+    fin = (rng.random(R) < 0.1).astype(np.uint8)
+    f_lo, p = oracle.token_interval(stored, tokens, temp=temp, top_k=top_k, top_p=top_p, finished=fin)
+    for i in range(R):
+        if fin[i]:
+            assert f_lo[i] == 0.0 and p[i] == 1.0
+            continue
+        keep = topk_keep(wide[i], top_k)
+        keep = nucleus_keep(wide[i], temp, top_p, keep)
+        q = np.zeros(V)
+        q[keep] = softmax64(wide[i][keep], temp)
+        assert abs(f_lo[i] - q[:tokens[i]].sum()) < 1e-12
+        assert abs(p[i] - q[tokens[i]]) < 1e-12
+    # a code inside the token's interval decodes to that token, with that interval
+    live = (p > 1e-9) & (fin == 0)
+    mid = f_lo + 0.5 * p
+    st = oracle.step(stored[live], mid[live], temp=temp, top_k=top_k, top_p=top_p)
+    assert np.array_equal(st["token"], tokens[live])
+    assert np.allclose(st["f_lo"], f_lo[live], rtol=0, atol=1e-15)
+    assert np.allclose(st["p"], p[live], rtol=1e-13, atol=0)
+
+
+def test_chained_token_intervals_give_the_sequence_interval():
+    P0 = [0.5, 0.2, 0.3]
+    Pc = [[0.1, 0.6, 0.3], [0.7, 0.1, 0.2], [0.25, 0.25, 0.5]]
+    E, U, V, scale = markov_model(P0, Pc)
+    for seq in [(0, 1, 2), (2, 2, 0), (1, 0, 0), (0, 0, 1)]:
+        w_ref, P_ref = oracle.encode(E, U, V, seq, scale=scale)
+        w, P, prev = 0.0, 1.0, V
+        for tok in seq:
+            row = oracle.bigram_logits(E, U, prev, scale=scale)
+            f_lo, p = oracle.token_interval(row[None, :], [tok])
+            w, P, prev = w + P * f_lo[0], P * p[0], tok
+        assert abs(w - w_ref) < 1e-15 and abs(P - P_ref) < 1e-15
+        # and it is the interval brute force assigns to that sequence
+        keys, starts, probs = enumerate_codebook(P0, Pc, 3)
+        at = keys.index(tuple(seq))
+        lo, hi = starts[at], starts[at] + probs[at]
+        assert abs(w - lo) < 1e-12 and abs(w + P - hi) < 1e-12
+
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f64"])
 @pytest.mark.parametrize("temp", [1.0, 0.7, 2.5])
