@@ -145,6 +145,31 @@ def main():
     if thr_n:
         out["threshold_kernel"] = {"avg_launch_us": thr_ms / thr_n * 1e3, "launches": thr_n}
 
+    # ---- encode direction (sequence -> code interval) over the sequences just decoded
+    lo = torch.empty(R, dtype=torch.float64, device="cuda")
+    width = torch.empty(R, dtype=torch.float64, device="cuda")
+    B.as_encode(ctx, model, prompts, N, T, tokens, temp, top_k, top_p, eos, lo, width)
+    torch.cuda.synchronize()
+    ctx.profile_read(3)
+    ctx.profile(True)
+    e0 = time.perf_counter()
+    for _ in range(3):
+        B.as_encode(ctx, model, prompts, N, T, tokens, temp, top_k, top_p, eos, lo, width)
+    torch.cuda.synchronize()
+    e1 = time.perf_counter()
+    iv_ms, iv_n, _ = ctx.profile_read(3)
+    ctx.profile_read(1); ctx.profile_read(2)
+    ctx.profile(False)
+    iv_us = iv_ms / max(iv_n, 1) * 1e3
+    out["encode"] = {
+        "kernel": "interval_kernel (lookup of a given token instead of a search), inside as_encode",
+        "avg_launch_us": iv_us, "launches": iv_n, "bound": "hbm",
+        "achieved": active_rows_per_launch * bytes_per_row / (iv_us * 1e-6) / 1e9 if iv_n else None,
+        "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "code_steps_per_s_with_dispatch_events": code_steps / args.steps * 3 / (e1 - e0)}
+    if out["encode"]["achieved"]:
+        out["encode"]["frac"] = out["encode"]["achieved"] / HBM_PEAK_GBS
+
     if args.copy_calibration:
         src_t = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda").random_()
         dst_t = torch.empty_like(src_t)

@@ -78,11 +78,11 @@ const char *as_last_error(const as_ctx *ctx);
 
 /*
  * Measurement aid (not part of the method): with profiling on, every launch of
- * the sampling kernel, the logits kernel and the threshold kernel carries its
+ * the sampling kernel, the logits, threshold and interval kernels carries its
  * own start/stop HIP events, taken from the dispatch on the context's stream.
  * as_ctx_profile_read synchronises the stream, returns the summed kernel time
  * and the number of timed launches since the last read for
- *   kernel 0: fused sampling step   1: logits (bigram) kernel   2: threshold
+ *   kernel 0: fused sampling step   1: logits (bigram) kernel   2: threshold   3: interval (encode) step
  * and resets the counters.  At most 16384 launches per kernel are timed between
  * reads; further ones run untimed and are counted in *untimed.  Any output
  * pointer may be NULL.  Switching profiling on makes the first launches create
@@ -198,6 +198,46 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts,
                     int32_t B, int32_t N, int32_t T, const float *u, float temp,
                     int32_t top_k, float top_p, int32_t eos_id,
                     int32_t *tokens_out, float *codes_out);
+
+/*
+ * Encode direction, one step (Sec. 4.1: the interval of a sequence is built by the
+ * codebook recursion; Sec. 3.1: a token's sub-interval starts at the cumulative
+ * probability of the tokens before it in vocabulary order and is as wide as its
+ * conditional probability).  For every row r with the row's kept, tempered softmax
+ *     lo[r]    += width[r] * F(tokens[r] - 1)
+ *     width[r] *= P(tokens[r])
+ * Start from lo = 0, width = 1; after the last token the codes in [lo, lo + width)
+ * are the ones as_step decodes to that sequence (up to the rounding of an fp32 code).
+ *   logits, rows, ld, temp, top_k, top_p, row_ids, logits_rows   as in as_step_ex
+ *   tokens        DEVICE int32[rows]; a token outside [0,V) or outside the kept set
+ *                 has probability zero (width becomes 0)
+ *   lo, width     DEVICE double[rows], read and written
+ *   finished_in   DEVICE uint8[rows] or NULL: nonzero rows are past their EOS
+ *                 (Sec. 3.3: padding) and are left unchanged
+ *   eos_id        < 0: none; required with finished_in
+ *   finished_out  DEVICE uint8[rows] or NULL: set where the row is or becomes finished
+ * Asynchronous on the context's stream; allocates nothing.
+ */
+as_status as_interval_step(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
+                           const int32_t *tokens, float temp, int32_t top_k, float top_p,
+                           double *lo, double *width, const uint8_t *finished_in,
+                           int32_t eos_id, uint8_t *finished_out, const int32_t *row_ids,
+                           int64_t logits_rows);
+
+/*
+ * Encode direction, whole sequences under the bigram model (Sec. 4.1): the interval
+ * [lo, lo + width) of each of the B*N token sequences, the inverse of as_decode.  Per
+ * step: logits for the previous token (the prompt's start token first), optional keep
+ * threshold, as_interval_step on column t of `tokens`; EOS is sticky as in as_decode.
+ *   prompts     DEVICE int32[B]
+ *   tokens      DEVICE int32[B, N, T], as written by as_decode
+ *   lo_out, width_out   DEVICE double[B*N]
+ * Uses (and may grow) the context's decode workspace.
+ */
+as_status as_encode(as_ctx *ctx, const as_model *model, const int32_t *prompts,
+                    int32_t B, int32_t N, int32_t T, const int32_t *tokens, float temp,
+                    int32_t top_k, float top_p, int32_t eos_id,
+                    double *lo_out, double *width_out);
 
 #ifdef __cplusplus
 }

@@ -45,12 +45,15 @@ def lib():
     L.as_model_destroy.argtypes = [vp]
     L.as_bigram_logits.argtypes = [vp, vp, vp, i64, vp, i64]
     L.as_decode.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, f32, i32, vp, vp]
+    L.as_interval_step.argtypes = [vp, vp, i64, i64, vp, f32, i32, f32, vp, vp, vp, i32, vp, vp, i64]
+    L.as_encode.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, f32, i32, vp, vp]
     L.as_ctx_profile.argtypes = [vp, C.c_int]
     L.as_ctx_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(i64)]
     L.as_ctx_profile.restype = C.c_int
     L.as_ctx_profile_read.restype = C.c_int
     for name in ("as_ctx_create", "as_ctx_destroy", "as_step", "as_step_ex", "as_lattice",
-                 "as_model_create_bigram", "as_model_destroy", "as_bigram_logits", "as_decode"):
+                 "as_model_create_bigram", "as_model_destroy", "as_bigram_logits", "as_decode",
+                 "as_interval_step", "as_encode"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -193,3 +196,23 @@ def as_decode(ctx, model, prompts, N, T, u, temp, top_k, top_p, eos_id, tokens_o
         _dev(u, torch.float32, "u", B), float(temp), int(top_k), float(top_p), int(eos_id),
         _dev(tokens_out, torch.int32, "tokens_out", B * int(N) * int(T)),
         _dev(codes_out, torch.float32, "codes_out", B * int(N))))
+
+
+def as_interval_step(ctx, logits, tokens, temp, top_k, top_p, lo, width, finished_in=None, eos_id=-1,
+                     finished_out=None, row_ids=None):
+    ptr, lrows, ld = _logits_args(ctx, logits)
+    rows = tokens.numel() if row_ids is not None else lrows
+    ctx._check(lib().as_interval_step(
+        ctx._h, ptr, rows, ld, _dev(tokens, torch.int32, "tokens", rows), float(temp), int(top_k), float(top_p),
+        _dev(lo, torch.float64, "lo", rows), _dev(width, torch.float64, "width", rows),
+        _dev(finished_in, torch.uint8, "finished_in", rows), int(eos_id),
+        _dev(finished_out, torch.uint8, "finished_out", rows), _dev(row_ids, torch.int32, "row_ids", rows), lrows))
+
+
+def as_encode(ctx, model, prompts, N, T, tokens, temp, top_k, top_p, eos_id, lo_out, width_out):
+    B = prompts.numel()
+    ctx._check(lib().as_encode(
+        ctx._h, model._h, _dev(prompts, torch.int32, "prompts"), B, int(N), int(T),
+        _dev(tokens, torch.int32, "tokens", B * int(N) * int(T)), float(temp), int(top_k), float(top_p),
+        int(eos_id), _dev(lo_out, torch.float64, "lo_out", B * int(N)),
+        _dev(width_out, torch.float64, "width_out", B * int(N))))

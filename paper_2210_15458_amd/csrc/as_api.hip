@@ -323,4 +323,88 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, 
     return AS_OK;
 }
 
+as_status as_interval_step(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, const int32_t *tokens,
+                           float temp, int32_t top_k, float top_p, double *lo, double *width,
+                           const uint8_t *finished_in, int32_t eos_id, uint8_t *finished_out,
+                           const int32_t *row_ids, int64_t logits_rows)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (rows < 0 || rows > ctx->max_rows) return fail(ctx, AS_ERR_INVALID_ARG, "rows outside [0, max_rows]");
+    if (rows == 0) return AS_OK;
+    if (!logits || !tokens || !lo || !width)
+        return fail(ctx, AS_ERR_INVALID_ARG, "logits, tokens, lo and width must not be NULL");
+    if (ld < ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "ld is smaller than the vocabulary");
+    if (!(temp > 0.f) || !isfinite(temp)) return fail(ctx, AS_ERR_INVALID_ARG, "temp must be finite and > 0");
+    if (row_ids && logits_rows < 1) return fail(ctx, AS_ERR_INVALID_ARG, "row_ids given but logits_rows < 1");
+    if (finished_in && eos_id < 0)
+        return fail(ctx, AS_ERR_INVALID_ARG, "finished_in given without an eos_id");
+    if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
+    if (isnan(top_p)) return fail(ctx, AS_ERR_INVALID_ARG, "top_p is NaN");
+
+    const float *thr = nullptr;
+    if (truncation_on(ctx->V, top_k, top_p)) {
+        as_status st = launch_threshold(ctx, logits, rows, ld, finished_in, row_ids, temp, top_k, top_p, ctx->thr);
+        if (st != AS_OK) return st;
+        thr = ctx->thr;
+    }
+    IntervalArgs a{};
+    a.logits = logits; a.rows = rows; a.ld = ld; a.V = ctx->V; a.dtype = ctx->dtype;
+    a.tokens = tokens; a.tok_stride = 1; a.k = 1.44269504088896340736f / temp; a.thr = thr;
+    a.finished_in = finished_in; a.eos_id = eos_id; a.finished_out = finished_out;
+    a.lo = lo; a.width = width; a.row_ids = row_ids; a.prev_out = nullptr;
+    return launch_interval(ctx, a);
+}
+
+as_status as_encode(as_ctx *ctx, const as_model *model, const int32_t *prompts, int32_t B, int32_t N, int32_t T,
+                    const int32_t *tokens, float temp, int32_t top_k, float top_p, int32_t eos_id,
+                    double *lo_out, double *width_out)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (!model) return fail(ctx, AS_ERR_INVALID_ARG, "model is NULL");
+    if (model->V != ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "model and context disagree on V");
+    if (B < 0 || N < 1 || T < 0) return fail(ctx, AS_ERR_INVALID_ARG, "B, T must be >= 0 and N >= 1");
+    const int64_t R = (int64_t)B * N;
+    if (R > ctx->max_rows) return fail(ctx, AS_ERR_INVALID_ARG, "B*N exceeds max_rows");
+    if (R == 0) return AS_OK;
+    if (!prompts || !lo_out || !width_out)
+        return fail(ctx, AS_ERR_INVALID_ARG, "prompts, lo_out and width_out must not be NULL");
+    if (T > 0 && !tokens) return fail(ctx, AS_ERR_INVALID_ARG, "tokens must not be NULL");
+    if (!(temp > 0.f) || !isfinite(temp)) return fail(ctx, AS_ERR_INVALID_ARG, "temp must be finite and > 0");
+    if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
+    if (isnan(top_p)) return fail(ctx, AS_ERR_INVALID_ARG, "top_p is NaN");
+
+    const size_t esz = ctx->dtype == AS_BF16 ? 2 : 4;
+    const int64_t ldw = ((int64_t)ctx->V + 7) / 8 * 8;        // rows start 16-byte aligned
+    as_status st = grow(ctx, ctx->logits, (size_t)R * ldw * esz);
+    if (st != AS_OK) return st;
+    st = grow(ctx, ctx->state, (size_t)R * 9);
+    if (st != AS_OK) return st;
+    float *codes = static_cast<float *>(ctx->state.ptr);      // (unused here; same layout as as_decode)
+    int32_t *prev = reinterpret_cast<int32_t *>(codes + R);
+    uint8_t *fin = reinterpret_cast<uint8_t *>(prev + R);
+
+    st = launch_interval_init(ctx, B, N, prompts, lo_out, width_out, prev, fin);
+    if (st != AS_OK) return st;
+    const bool trunc = truncation_on(ctx->V, top_k, top_p);
+    for (int32_t t = 0; t < T; ++t) {
+        st = launch_bigram_logits(ctx, model, prev, R, ctx->logits.ptr, ldw);
+        if (st != AS_OK) return st;
+        if (trunc) {
+            st = launch_threshold(ctx, ctx->logits.ptr, R, ldw, eos_id >= 0 ? fin : nullptr, nullptr, temp,
+                                  top_k, top_p, ctx->thr);
+            if (st != AS_OK) return st;
+        }
+        IntervalArgs a{};
+        a.logits = ctx->logits.ptr; a.rows = R; a.ld = ldw; a.V = ctx->V; a.dtype = ctx->dtype;
+        a.tokens = tokens + t; a.tok_stride = T; a.k = 1.44269504088896340736f / temp;
+        a.thr = trunc ? ctx->thr : nullptr;
+        a.finished_in = eos_id >= 0 ? fin : nullptr; a.eos_id = eos_id;
+        a.finished_out = eos_id >= 0 ? fin : nullptr;
+        a.lo = lo_out; a.width = width_out; a.row_ids = nullptr; a.prev_out = prev;
+        st = launch_interval(ctx, a);
+        if (st != AS_OK) return st;
+    }
+    return AS_OK;
+}
+
 }  // extern "C"

@@ -25,7 +25,7 @@ struct DeviceBuf {
 // Optional per-kernel timing: when switched on, every launch of a profiled
 // kernel carries its own start/stop events (taken from the dispatch itself,
 // not from separate stream markers), read back by as_ctx_profile_read.
-enum KernelId { kKernelStep = 0, kKernelLogits = 1, kKernelThreshold = 2, kKernelCount = 3 };
+enum KernelId { kKernelStep = 0, kKernelLogits = 1, kKernelThreshold = 2, kKernelInterval = 3, kKernelCount = 4 };
 constexpr size_t kProfileCapacity = 16384;      // timed launches per kernel between reads
 
 struct ProfileSlot {
@@ -34,8 +34,8 @@ struct ProfileSlot {
 struct Profile {
     bool on = false;
     std::vector<ProfileSlot> slots[kKernelCount];   // created on demand, reused after a read
-    size_t used[kKernelCount] = {0, 0, 0};
-    size_t dropped[kKernelCount] = {0, 0, 0};
+    size_t used[kKernelCount] = {};
+    size_t dropped[kKernelCount] = {};
 };
 
 }  // namespace as
@@ -118,7 +118,29 @@ struct StepArgs {
     int32_t *prev_out;           // decode state: next step's conditioning token, or null
 };
 
+struct IntervalArgs {
+    const void *logits;
+    int64_t rows;
+    int64_t ld;
+    int32_t V;
+    as_dtype dtype;
+    const int32_t *tokens;
+    int64_t tok_stride;          // token of row r at tokens[r * tok_stride]
+    float k;                     // log2(e)/temp
+    const float *thr;            // per-row keep threshold on raw logits, or null
+    const uint8_t *finished_in;
+    int32_t eos_id;
+    uint8_t *finished_out;
+    double *lo;                  // [rows] in/out
+    double *width;               // [rows] in/out
+    const int32_t *row_ids;
+    int32_t *prev_out;           // encode state: next step's conditioning token, or null
+};
+
 as_status launch_step(as_ctx *ctx, const StepArgs &a);
+as_status launch_interval(as_ctx *ctx, const IntervalArgs &a);
+as_status launch_interval_init(as_ctx *ctx, int32_t B, int32_t N, const int32_t *prompts, double *lo,
+                               double *width, int32_t *prev, uint8_t *finished);
 as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
                            const uint8_t *finished_in, const int32_t *row_ids,
                            float temp, int32_t top_k, float top_p, float *thr_out);

@@ -1,0 +1,185 @@
+// Encode direction: the interval of a given token sequence (Sec. 4.1, the
+// codebook recursion; Sec. 3.1 for one token's sub-interval).  Per step and row,
+// with the row's kept, tempered softmax in vocabulary order,
+//     lo    += width * F(token - 1)      (mass of the tokens before it)
+//     width *= P(token)
+// so that after the last step the codes in [lo, lo + width) are exactly the ones
+// that decode to the sequence.  The per-row pass is the one of the sampling step
+// with the search replaced by a lookup: weights exp2(x*k - ref) in fp32 against an
+// integer reference ref >= max x*k, sums in fp64.  lo and width are fp64 state.
+#include <type_traits>
+
+#include "as_common.hpp"
+
+namespace as {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(uint16_t h) { return __builtin_bit_cast(float, (uint32_t)h << 16); }
+
+// g(v0, x[0..n)) over the row's logits in runs of up to 8 consecutive ones starting at v0, each logit exactly
+// once per thread block.  Rows that can be read in 16-byte pieces are (VEC): four pieces in flight per
+// thread; the others go element by element.
+template <class T, bool VEC, class G>
+__device__ __forceinline__ void for_row(const T *row, int32_t V, G g)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int EPP = 16 / (int)sizeof(T);
+    if constexpr (VEC) {
+        const int32_t npieces = (V + EPP - 1) / EPP;
+        for (int32_t base = threadIdx.x; base < npieces; base += 4 * kThreads) {
+            u32x4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int32_t piece = base + u * kThreads;
+                w[u] = piece < npieces ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + piece)
+                                       : u32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int32_t piece = base + u * kThreads;
+                if (piece >= npieces) break;
+                const int32_t v0 = piece * EPP;
+                float x[EPP];
+#pragma unroll
+                for (int e = 0; e < EPP; ++e) {
+                    if constexpr (sizeof(T) == 2) {
+                        const uint32_t word = w[u][e >> 1];
+                        x[e] = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
+                    } else {
+                        const uint32_t word = w[u][e];
+                        x[e] = __builtin_bit_cast(float, word);
+                    }
+                }
+                const int n = V - v0 < EPP ? V - v0 : EPP;
+                g(v0, x, n, std::integral_constant<int, EPP>{});
+            }
+        }
+    } else {
+        for (int32_t v = threadIdx.x; v < V; v += kThreads) {
+            float x[1] = {widen(row[v])};
+            g(v, x, 1, std::integral_constant<int, 1>{});
+        }
+    }
+}
+
+// block-wide sum in a fixed order: lanes by the wave scan, then the waves in index order
+__device__ __forceinline__ double block_sum(double x, double *scratch)
+{
+    x = wave_sum(x);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = x;
+    __syncthreads();
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) t += scratch[w];
+    return t;
+}
+
+template <class T, bool VEC>
+__global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
+{
+    __shared__ double scratch[kThreads / 64];
+    __shared__ float fscratch[kThreads / 64];
+    const int64_t r = blockIdx.x;
+    const int32_t tok = a.tokens[r * a.tok_stride];
+    if (a.finished_in != nullptr && a.finished_in[r] != 0) {
+        // past its EOS: the position is padding and does not narrow the interval
+        if (threadIdx.x == 0) {
+            if (a.finished_out) a.finished_out[r] = 1;
+            if (a.prev_out) a.prev_out[r] = a.eos_id;
+        }
+        return;
+    }
+    const int64_t src = a.row_ids ? (int64_t)a.row_ids[r] : r;
+    const T *row = reinterpret_cast<const T *>(a.logits) + src * a.ld;
+    const float thr = a.thr ? a.thr[r] : -__builtin_inff();
+    const float k = a.k;
+
+    float m = -__builtin_inff();
+    for_row<T, VEC>(row, a.V, [&](int32_t, const float *x, int n, auto cap) {
+#pragma unroll
+        for (int e = 0; e < decltype(cap)::value; ++e)
+            if (e < n && x[e] >= thr) m = fmaxf(m, x[e]);
+    });
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) fscratch[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fscratch[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fscratch[w]);
+    const float ref = fmaxf(ceilf(m * k), -100000.f);
+
+    // per run: fp32 sums of at most 8 weights, then one fp64 add per total
+    double all = 0.0, before = 0.0, at = 0.0;
+    for_row<T, VEC>(row, a.V, [&](int32_t v0, const float *x, int n, auto cap) {
+        float s_all = 0.f, s_before = 0.f;
+#pragma unroll
+        for (int e = 0; e < decltype(cap)::value; ++e) {
+            const float w = (e < n && x[e] >= thr) ? __builtin_amdgcn_exp2f(fmaf(x[e], k, -ref)) : 0.f;
+            s_all += w;
+            s_before += v0 + e < tok ? w : 0.f;
+            if (v0 + e == tok) at = (double)w;
+        }
+        all += (double)s_all;
+        before += (double)s_before;
+    });
+    all = block_sum(all, scratch);
+    before = block_sum(before, scratch);
+    at = block_sum(at, scratch);
+    if (threadIdx.x == 0) {
+        // a token outside the vocabulary or outside the kept set has probability zero
+        const double f_lo = all > 0.0 ? before / all : 0.0;
+        const double p = (all > 0.0 && tok >= 0 && tok < a.V) ? at / all : 0.0;
+        const double w = a.width[r];
+        a.lo[r] += w * f_lo;
+        a.width[r] = w * p;
+        if (a.finished_out) a.finished_out[r] = (a.eos_id >= 0 && tok == a.eos_id) ? 1 : 0;
+        if (a.prev_out) a.prev_out[r] = (tok >= 0 && tok < a.V) ? tok : 0;
+    }
+}
+
+__global__ void interval_init_kernel(int32_t B, int32_t N, const int32_t *prompts, double *lo, double *width,
+                                     int32_t *prev, uint8_t *finished)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)B * N) return;
+    lo[idx] = 0.0;
+    width[idx] = 1.0;
+    prev[idx] = prompts[idx / N];
+    finished[idx] = 0;
+}
+
+}  // namespace
+
+as_status launch_interval(as_ctx *ctx, const IntervalArgs &a)
+{
+    if (a.rows == 0) return AS_OK;
+    const size_t esz = a.dtype == AS_BF16 ? 2 : 4;
+    const bool vec = reinterpret_cast<uintptr_t>(a.logits) % 16 == 0 && (a.ld * esz) % 16 == 0;
+    const dim3 grid((unsigned)a.rows), block(kThreads);
+    if (a.dtype == AS_BF16) {
+        if (vec) launch(ctx, kKernelInterval, interval_kernel<uint16_t, true>, grid, block, 0, a);
+        else launch(ctx, kKernelInterval, interval_kernel<uint16_t, false>, grid, block, 0, a);
+    } else {
+        if (vec) launch(ctx, kKernelInterval, interval_kernel<float, true>, grid, block, 0, a);
+        else launch(ctx, kKernelInterval, interval_kernel<float, false>, grid, block, 0, a);
+    }
+    AS_HIP_TRY(ctx, hipGetLastError());
+    return AS_OK;
+}
+
+as_status launch_interval_init(as_ctx *ctx, int32_t B, int32_t N, const int32_t *prompts, double *lo,
+                               double *width, int32_t *prev, uint8_t *finished)
+{
+    const int64_t n = (int64_t)B * N;
+    if (n == 0) return AS_OK;
+    hipLaunchKernelGGL(interval_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, B, N,
+                       prompts, lo, width, prev, finished);
+    AS_HIP_TRY(ctx, hipGetLastError());
+    return AS_OK;
+}
+
+}  // namespace as

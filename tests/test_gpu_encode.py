@@ -1,0 +1,172 @@
+"""GPU parity of the encode direction (sequence -> code interval, Sec. 4.1) against the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2210_15458_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-5          # relative tolerance on a token's probability (fp32 weights, fp64 sums)
+ABS_F = 2e-6        # absolute tolerance on a cumulative probability in [0, 1]
+
+
+def _interval_step(stored, tokens, V, temp=1.0, top_k=0, top_p=1.0, finished=None, eos_id=-1, lo0=None, w0=None):
+    import torch
+    from paper_2210_15458_amd import binding as B
+    from gpu_util import to_dev_logits
+    logits = to_dev_logits(stored)
+    R = tokens.shape[0]
+    ctx = B.Ctx(R, V, logits.dtype)
+    lo = torch.from_numpy(np.zeros(R) if lo0 is None else lo0.copy()).cuda()
+    w = torch.from_numpy(np.ones(R) if w0 is None else w0.copy()).cuda()
+    fin_in = None if finished is None else torch.from_numpy(finished.astype(np.uint8)).cuda()
+    fin_out = torch.full((R,), 7, dtype=torch.uint8, device="cuda") if eos_id >= 0 else None
+    B.as_interval_step(ctx, logits, torch.from_numpy(tokens.astype(np.int32)).cuda(), temp, top_k, top_p, lo, w,
+                       finished_in=fin_in, eos_id=eos_id, finished_out=fin_out)
+    torch.cuda.synchronize()
+    ctx.close()
+    return lo.cpu().numpy(), w.cpu().numpy(), None if fin_out is None else fin_out.cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V,ld", [(32128, None), (1001, None), (1001, 1008), (5, None), (256000, None)])
+@pytest.mark.parametrize("temp,top_k,top_p", [(1.0, 0, 1.0), (0.7, 0, 1.0), (1.0, 40, 1.0), (1.0, 0, 0.9)])
+def test_interval_step_matches_oracle(dtype, V, ld, temp, top_k, top_p):
+    import oracle
+    if V == 256000 and (dtype == "f32" or top_k or top_p < 1.0 or temp != 1.0):
+        pytest.skip("large vocabulary: one plain case is enough")
+    R = 24 if V > 100000 else 48
+    stored = synth.gaussian_logits(R, V, sigma=3.0, seed=V + 5, dtype=dtype, ld=ld)
+    rng = np.random.default_rng(V)
+    # half the tokens where the mass is (decoded from uniform codes), half anywhere
+    codes = rng.random(R)
+    likely = oracle.step(stored, codes, temp=temp, top_k=top_k, top_p=top_p, V=V)["token"]
+    tokens = np.where(np.arange(R) % 2 == 0, likely, rng.integers(0, V, R)).astype(np.int32)
+    f_lo, p = oracle.token_interval(stored, tokens, temp=temp, top_k=top_k, top_p=top_p, V=V, nthreads=8)
+    nuc = oracle.step(stored, codes, temp=temp, top_k=top_k, top_p=top_p, V=V)["nuc_margin"]
+    lo0 = rng.random(R) * 0.5
+    w0 = rng.random(R) * 0.5
+    lo, w, _ = _interval_step(stored, tokens, V, temp=temp, top_k=top_k, top_p=top_p, lo0=lo0, w0=w0)
+    for r in range(R):
+        if top_p < 1.0 and nuc[r] <= 1e-5:
+            continue                                   # kept set itself is a coin toss at the nucleus boundary
+        assert abs(w[r] - w0[r] * p[r]) <= REL * w0[r] * p[r] + 1e-300, (r, w[r], w0[r] * p[r])
+        assert abs(lo[r] - (lo0[r] + w0[r] * f_lo[r])) <= w0[r] * ABS_F + 1e-15, (r, lo[r], f_lo[r])
+
+
+def test_interval_step_finished_rows_and_bad_tokens():
+    import oracle
+    V, R, eos = 1000, 40, 3
+    stored = synth.gaussian_logits(R, V, sigma=3.0, seed=9, dtype="bf16")
+    rng = np.random.default_rng(9)
+    tokens = rng.integers(0, V, R).astype(np.int32)
+    tokens[5] = eos
+    tokens[6] = -1          # outside the vocabulary: probability zero
+    tokens[7] = V + 3
+    fin = (rng.random(R) < 0.3)
+    fin[5] = fin[6] = fin[7] = False
+    lo, w, fout = _interval_step(stored, tokens, V, finished=fin, eos_id=eos)
+    f_lo, p = oracle.token_interval(stored, np.clip(tokens, 0, V - 1), V=V, finished=fin.astype(np.uint8))
+    for r in range(R):
+        if fin[r]:
+            assert lo[r] == 0.0 and w[r] == 1.0 and fout[r] == 1
+        elif r in (6, 7):
+            assert w[r] == 0.0 and fout[r] == 0
+        else:
+            assert abs(w[r] - p[r]) <= REL * p[r] and abs(lo[r] - f_lo[r]) <= ABS_F
+            assert fout[r] == (1 if tokens[r] == eos else 0)
+
+
+def _model(V, d, dtype, seed=0):
+    import torch
+    from paper_2210_15458_amd import binding as B
+    from gpu_util import to_dev_logits
+    E, U = synth.bigram_weights(V, d, seed=seed, dtype=dtype)
+    Ed, Ud = to_dev_logits(E), to_dev_logits(U)
+    model = B.Model(Ed, Ud, scale=3.0)
+    torch.cuda.synchronize()
+    return E, U, Ed, model
+
+
+@pytest.mark.parametrize("cfg_id,T", [(0, 8), (1, 3)])
+def test_encode_inverts_decode(cfg_id, T):
+    """The interval of a decoded sequence contains the code it was decoded from (Sec. 4.1), for as long as
+    the interval is wide against the rounding of an fp32 code."""
+    import torch
+    from paper_2210_15458_amd import binding as B
+    cfg = synth.CONFIGS[cfg_id]
+    V, d, Bn, N = cfg["V"], cfg["d"], cfg["B"], cfg["N"]
+    tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    E, U, Ed, model = _model(V, d, cfg["dtype"])
+    R = Bn * N
+    ctx = B.Ctx(R, V, tdt)
+    prompts = torch.from_numpy(synth.prompts(Bn, V, seed=1)).cuda()
+    u = torch.from_numpy(synth.shifts(Bn, seed=2)).cuda()
+    codes0 = torch.empty(R, dtype=torch.float32, device="cuda")
+    B.as_lattice(ctx, u, N, codes0)
+    inside = total = 0
+    for t_len in range(1, T + 1):
+        tokens = torch.empty((Bn, N, t_len), dtype=torch.int32, device="cuda")
+        B.as_decode(ctx, model, prompts, N, t_len, u, cfg["temp"], 0, 1.0, cfg["eos_id"], tokens)
+        lo = torch.empty(R, dtype=torch.float64, device="cuda")
+        w = torch.empty(R, dtype=torch.float64, device="cuda")
+        B.as_encode(ctx, model, prompts, N, t_len, tokens, cfg["temp"], 0, 1.0, cfg["eos_id"], lo, w)
+        torch.cuda.synchronize()
+        c = codes0.cpu().numpy().astype(np.float64)
+        lo_h, w_h = lo.cpu().numpy(), w.cpu().numpy()
+        assert np.all(w_h > 0) and np.all(lo_h >= 0) and np.all(lo_h + w_h <= 1 + 1e-9)
+        wide = w_h > 1e-4                                   # the fp32 decode has resolved this interval cleanly
+        slack = 2e-6                                        # cumulative rounding of the fp32 path, code units
+        ok = (c >= lo_h - slack) & (c < lo_h + w_h + slack)
+        assert np.all(ok[wide]), (t_len, int((~ok & wide).sum()))
+        inside += int(ok[wide].sum()); total += int(wide.sum())
+    print("codes inside their sequence's interval:", inside, "of", total, flush=True)
+    assert total > R
+    ctx.close(); model.close()
+
+
+def test_encode_matches_oracle_on_tiny_config():
+    import torch
+    import oracle
+    from paper_2210_15458_amd import binding as B
+    cfg = synth.CONFIGS[0]
+    V, d, Bn, N, T = cfg["V"], cfg["d"], cfg["B"], cfg["N"], cfg["T"]
+    E, U, Ed, model = _model(V, d, cfg["dtype"])
+    R = Bn * N
+    ctx = B.Ctx(R, V, torch.float32)
+    prompts_h = synth.prompts(Bn, V, seed=1)
+    rng = np.random.default_rng(3)
+    tokens_h = rng.integers(0, V, (Bn, N, T)).astype(np.int32)
+    for eos in (-1, 1):
+        lo = torch.empty(R, dtype=torch.float64, device="cuda")
+        w = torch.empty(R, dtype=torch.float64, device="cuda")
+        B.as_encode(ctx, model, torch.from_numpy(prompts_h).cuda(), N, T, torch.from_numpy(tokens_h).cuda(), 1.0, 0,
+                    1.0, eos, lo, w)
+        torch.cuda.synchronize()
+        lo_h, w_h = lo.cpu().numpy(), w.cpu().numpy()
+        for r in range(R):
+            w_ref, P_ref = oracle.encode(E, U, int(prompts_h[r // N]), tokens_h.reshape(R, T)[r], eos_id=eos)
+            # fp32 logits from an fp32 dot product against fp64: relative 1e-5 per step
+            assert abs(w_h[r] - P_ref) <= 1e-5 * T * P_ref, (eos, r)
+            assert abs(lo_h[r] - w_ref) <= 1e-6 * T, (eos, r)
+    ctx.close(); model.close()
+
+
+def test_interval_argument_errors():
+    import torch
+    from paper_2210_15458_amd import binding as B
+    ctx = B.Ctx(8, 100, torch.float32)
+    logits = torch.zeros((4, 104), dtype=torch.float32, device="cuda")
+    tok = torch.zeros(4, dtype=torch.int32, device="cuda")
+    lo = torch.zeros(4, dtype=torch.float64, device="cuda")
+    w = torch.ones(4, dtype=torch.float64, device="cuda")
+    with pytest.raises(B.ArithSamplingError):
+        B.as_interval_step(ctx, logits, tok, 0.0, 0, 1.0, lo, w)
+    with pytest.raises(B.ArithSamplingError):
+        B.as_interval_step(ctx, logits, tok, 1.0, 0, 1.0, lo, w, finished_in=torch.zeros(4, dtype=torch.uint8, device="cuda"))
+    B.as_interval_step(ctx, logits, tok, 1.0, 0, 1.0, lo, w)
+    torch.cuda.synchronize()
+    assert np.allclose(w.cpu().numpy(), 0.01) and np.all(lo.cpu().numpy() == 0.0)
+    ctx.close()
