@@ -200,6 +200,34 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts,
                     int32_t *tokens_out, float *codes_out);
 
 /*
+ * Ancestral sampling with the same kernels (Sec. 3.3; Sec. 3.1, last paragraph: with a
+ * fresh uniform per step the bucket search is inverse-CDF categorical sampling).  As
+ * as_decode, except that the code of row r at step t is uniforms[t*B*N + r] and the
+ * rescaled code is dropped.  The caller draws the uniforms (the library holds no
+ * random number generator).
+ *   uniforms    DEVICE float[T, B*N], each in [0,1)
+ *   others      as in as_decode
+ */
+as_status as_decode_ancestral(as_ctx *ctx, const as_model *model, const int32_t *prompts,
+                              int32_t B, int32_t N, int32_t T, const float *uniforms,
+                              float temp, int32_t top_k, float top_p, int32_t eos_id,
+                              int32_t *tokens_out);
+
+/*
+ * The estimator of Sec. 4.2, (1/N) sum_i s(x_i), per prompt, for additive per-token
+ * scores: s(x) = sum of score[x_t] over the tokens of x up to and including its first
+ * eos_id (the rest is padding, Sec. 3.3).  fp64 sums in a fixed order.
+ *   tokens      DEVICE int32[B, N, T] (as written by as_decode / as_decode_ancestral);
+ *               tokens outside [0,V) score 0
+ *   score       DEVICE float[V]
+ *   eos_id      < 0: none
+ *   est_out     DEVICE double[B]
+ * Asynchronous on the context's stream; allocates nothing.
+ */
+as_status as_estimate_mean(as_ctx *ctx, const int32_t *tokens, int32_t B, int32_t N,
+                           int32_t T, const float *score, int32_t eos_id, double *est_out);
+
+/*
  * Encode direction, one step (Sec. 4.1: the interval of a sequence is built by the
  * codebook recursion; Sec. 3.1: a token's sub-interval starts at the cumulative
  * probability of the tokens before it in vocabulary order and is as wide as its

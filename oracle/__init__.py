@@ -55,6 +55,9 @@ def lib():
             C.c_void_p, C.c_double, C.c_int32, C.c_double, C.c_void_p,
             C.c_void_p, C.c_void_p, C.c_int]
         L.ao_token_interval_rows.restype = C.c_int
+        L.ao_estimate_mean.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                       C.c_void_p]
+        L.ao_estimate_mean.restype = None
         L.ao_max_threads.argtypes = []
         L.ao_max_threads.restype = C.c_int
         _lib = L
@@ -163,6 +166,16 @@ def decode(E, U, prompts, N, T, codes0, temp=1.0, top_k=0, top_p=1.0,
         out["p"] = p.reshape(B, N, T)
         out["delta"] = dl.reshape(B, N, T)
     return out
+
+
+def estimate_mean(tokens, score, eos_id=-1):
+    """(1/N) sum_i s(x_i) per prompt for tokens [B, N, T] and additive per-token scores score[V]."""
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    B, N, T = tokens.shape
+    score = np.ascontiguousarray(score, dtype=np.float64)
+    est = np.empty(B, dtype=np.float64)
+    lib().ao_estimate_mean(_ptr(tokens), B, N, T, _ptr(score), int(eos_id), _ptr(est))
+    return est
 
 
 def token_interval(stored, tokens, temp=1.0, top_k=0, top_p=1.0, V=None,

@@ -542,6 +542,30 @@ int ao_encode(const void *E, const void *U, int wdtype, int32_t V, int32_t d,
     return 0;
 }
 
+/*
+ * The estimator of Sec. 4.2, (1/N) sum_i s(x_i), per prompt, for additive
+ * per-token scores: s(x) = sum of score[x_t] over the sequence's tokens up to
+ * and including its first eos_id (the rest is padding, Sec. 3.3).  tokens is
+ * [B, N, T]; est is [B].
+ */
+void ao_estimate_mean(const int32_t *tokens, int32_t B, int32_t N, int32_t T,
+                      const double *score, int32_t eos_id, double *est)
+{
+    for (int32_t b = 0; b < B; ++b) {
+        double total = 0.0;
+        for (int32_t i = 0; i < N; ++i) {
+            const int32_t *seq = tokens + ((int64_t)b * N + i) * T;
+            double s = 0.0;
+            for (int32_t t = 0; t < T; ++t) {
+                s += score[seq[t]];
+                if (eos_id >= 0 && seq[t] == eos_id) break;
+            }
+            total += s;
+        }
+        est[b] = total / (double)N;
+    }
+}
+
 int ao_max_threads(void)
 {
 #ifdef _OPENMP

@@ -47,13 +47,15 @@ def lib():
     L.as_decode.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, f32, i32, vp, vp]
     L.as_interval_step.argtypes = [vp, vp, i64, i64, vp, f32, i32, f32, vp, vp, vp, i32, vp, vp, i64]
     L.as_encode.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, f32, i32, vp, vp]
+    L.as_decode_ancestral.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, f32, i32, vp]
+    L.as_estimate_mean.argtypes = [vp, vp, i32, i32, i32, vp, i32, vp]
     L.as_ctx_profile.argtypes = [vp, C.c_int]
     L.as_ctx_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(i64)]
     L.as_ctx_profile.restype = C.c_int
     L.as_ctx_profile_read.restype = C.c_int
     for name in ("as_ctx_create", "as_ctx_destroy", "as_step", "as_step_ex", "as_lattice",
                  "as_model_create_bigram", "as_model_destroy", "as_bigram_logits", "as_decode",
-                 "as_interval_step", "as_encode"):
+                 "as_interval_step", "as_encode", "as_decode_ancestral", "as_estimate_mean"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -216,3 +218,20 @@ def as_encode(ctx, model, prompts, N, T, tokens, temp, top_k, top_p, eos_id, lo_
         _dev(tokens, torch.int32, "tokens", B * int(N) * int(T)), float(temp), int(top_k), float(top_p),
         int(eos_id), _dev(lo_out, torch.float64, "lo_out", B * int(N)),
         _dev(width_out, torch.float64, "width_out", B * int(N))))
+
+
+def as_decode_ancestral(ctx, model, prompts, N, T, uniforms, temp, top_k, top_p, eos_id, tokens_out):
+    B = prompts.numel()
+    ctx._check(lib().as_decode_ancestral(
+        ctx._h, model._h, _dev(prompts, torch.int32, "prompts"), B, int(N), int(T),
+        _dev(uniforms, torch.float32, "uniforms", B * int(N) * int(T)), float(temp), int(top_k), float(top_p),
+        int(eos_id), _dev(tokens_out, torch.int32, "tokens_out", B * int(N) * int(T))))
+
+
+def as_estimate_mean(ctx, tokens, score, eos_id, est_out):
+    if tokens.dim() != 3:
+        raise ValueError("tokens must be [B, N, T]")
+    B, N, T = tokens.shape
+    ctx._check(lib().as_estimate_mean(
+        ctx._h, _dev(tokens, torch.int32, "tokens"), B, N, T, _dev(score, torch.float32, "score", ctx.V),
+        int(eos_id), _dev(est_out, torch.float64, "est_out", B)))

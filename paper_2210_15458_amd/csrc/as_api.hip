@@ -269,9 +269,11 @@ as_status as_bigram_logits(as_ctx *ctx, const as_model *model, const int32_t *pr
     return launch_bigram_logits(ctx, model, prev, rows, logits_out, ld);
 }
 
-as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, int32_t B, int32_t N, int32_t T,
-                    const float *u, float temp, int32_t top_k, float top_p, int32_t eos_id, int32_t *tokens_out,
-                    float *codes_out)
+// as_decode and as_decode_ancestral: with `uniforms` the code of row r at step t is uniforms[t*R + r] and
+// the rescaled code is dropped, otherwise codes start on the lattice of u and are carried from step to step.
+static as_status decode_impl(as_ctx *ctx, const as_model *model, const int32_t *prompts, int32_t B, int32_t N,
+                             int32_t T, const float *u, const float *uniforms, float temp, int32_t top_k,
+                             float top_p, int32_t eos_id, int32_t *tokens_out, float *codes_out)
 {
     if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
     if (!model) return fail(ctx, AS_ERR_INVALID_ARG, "model is NULL");
@@ -280,7 +282,7 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, 
     const int64_t R = (int64_t)B * N;
     if (R > ctx->max_rows) return fail(ctx, AS_ERR_INVALID_ARG, "B*N exceeds max_rows");
     if (R == 0) return AS_OK;
-    if (!prompts || !u) return fail(ctx, AS_ERR_INVALID_ARG, "prompts and u must not be NULL");
+    if (!prompts || (!u && !uniforms)) return fail(ctx, AS_ERR_INVALID_ARG, "prompts and u must not be NULL");
     if (T > 0 && !tokens_out) return fail(ctx, AS_ERR_INVALID_ARG, "tokens_out must not be NULL");
     if (!(temp > 0.f) || !isfinite(temp)) return fail(ctx, AS_ERR_INVALID_ARG, "temp must be finite and > 0");
     if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
@@ -296,7 +298,7 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, 
     int32_t *prev = reinterpret_cast<int32_t *>(codes + R);
     uint8_t *fin = reinterpret_cast<uint8_t *>(prev + R);
 
-    st = launch_lattice(ctx, u, B, N, codes, prompts, prev, fin);
+    st = launch_lattice(ctx, u, B, N, uniforms ? nullptr : codes, prompts, prev, fin);
     if (st != AS_OK) return st;
     const bool trunc = truncation_on(ctx->V, top_k, top_p);
     for (int32_t t = 0; t < T; ++t) {
@@ -309,7 +311,7 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, 
         }
         StepArgs a{};
         a.logits = ctx->logits.ptr; a.rows = R; a.ld = ldw; a.V = ctx->V; a.dtype = ctx->dtype;
-        a.codes = codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = trunc ? ctx->thr : nullptr;
+        a.codes = uniforms ? uniforms + (int64_t)t * R : codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = trunc ? ctx->thr : nullptr;
         a.tokens_out = tokens_out + t; a.tok_stride = T; a.codes_out = codes;
         a.finished_in = eos_id >= 0 ? fin : nullptr; a.eos_id = eos_id;
         a.finished_out = eos_id >= 0 ? fin : nullptr;
@@ -321,6 +323,36 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, 
         AS_HIP_TRY(ctx, hipMemcpyAsync(codes_out, codes, (size_t)R * sizeof(float), hipMemcpyDeviceToDevice,
                                        ctx->stream));
     return AS_OK;
+}
+
+as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts, int32_t B, int32_t N, int32_t T,
+                    const float *u, float temp, int32_t top_k, float top_p, int32_t eos_id, int32_t *tokens_out,
+                    float *codes_out)
+{
+    if (ctx && !u) return fail(ctx, AS_ERR_INVALID_ARG, "prompts and u must not be NULL");
+    return decode_impl(ctx, model, prompts, B, N, T, u, nullptr, temp, top_k, top_p, eos_id, tokens_out, codes_out);
+}
+
+as_status as_decode_ancestral(as_ctx *ctx, const as_model *model, const int32_t *prompts, int32_t B, int32_t N,
+                              int32_t T, const float *uniforms, float temp, int32_t top_k, float top_p,
+                              int32_t eos_id, int32_t *tokens_out)
+{
+    if (ctx && !uniforms && (int64_t)B * N * T > 0)
+        return fail(ctx, AS_ERR_INVALID_ARG, "uniforms must not be NULL");
+    return decode_impl(ctx, model, prompts, B, N, T, nullptr, uniforms, temp, top_k, top_p, eos_id, tokens_out,
+                       nullptr);
+}
+
+as_status as_estimate_mean(as_ctx *ctx, const int32_t *tokens, int32_t B, int32_t N, int32_t T, const float *score,
+                           int32_t eos_id, double *est_out)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (B < 0 || N < 1 || T < 0) return fail(ctx, AS_ERR_INVALID_ARG, "B, T must be >= 0 and N >= 1");
+    if (B == 0) return AS_OK;
+    if (!score || !est_out || (T > 0 && !tokens))
+        return fail(ctx, AS_ERR_INVALID_ARG, "tokens, score and est_out must not be NULL");
+    if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
+    return launch_estimate(ctx, tokens, B, N, T, score, eos_id, est_out);
 }
 
 as_status as_interval_step(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, const int32_t *tokens,

@@ -146,6 +146,8 @@ as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_
                            float temp, int32_t top_k, float top_p, float *thr_out);
 as_status launch_lattice(as_ctx *ctx, const float *u, int32_t B, int32_t N, float *codes_out,
                          const int32_t *prompts, int32_t *prev_out, uint8_t *finished_out);
+as_status launch_estimate(as_ctx *ctx, const int32_t *tokens, int32_t B, int32_t N, int32_t T, const float *score,
+                          int32_t eos_id, double *est_out);
 as_status launch_transpose(const void *U, void *Ut, int32_t d, int32_t V, as_dtype wdtype);
 as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *prev,
                                int64_t rows, void *logits_out, int64_t ld);

@@ -22,8 +22,8 @@ __global__ void lattice_kernel(const float *u, int32_t B, int32_t N, float *code
     if (idx >= (int64_t)B * N) return;
     const int32_t b = (int32_t)(idx / N), i = (int32_t)(idx % N);
     // c_i = (i + u)/N: spacing exactly 1/N around the circle, one shift per prompt
-    const double c = ((double)i + (double)u[b]) / (double)N;
-    codes[idx] = fminf((float)c, 0x1.fffffep-1f);
+    const double c = codes ? ((double)i + (double)u[b]) / (double)N : 0.0;
+    if (codes) codes[idx] = fminf((float)c, 0x1.fffffep-1f);
     if (prev) prev[idx] = prompts[b];
     if (finished) finished[idx] = 0;
 }
@@ -597,6 +597,32 @@ void launch_dot(as_ctx *ctx, const as_model *m, const int32_t *prev, int64_t row
            (const WT *)m->E, (const WT *)m->Ut, prev, rows, m->V, m->d, alpha, (OutT *)out, ld);
 }
 
+// ------------------------------------------------------------------ estimator
+
+// (1/N) sum_i s(x_i) per prompt (Sec. 4.2) for additive per-token scores: s(x) = sum of score[x_t] up to
+// and including the first EOS.  One block per prompt; fp64 sums in a fixed order.
+__global__ __launch_bounds__(256) void estimate_kernel(const int32_t *tokens, int32_t N, int32_t T, int32_t V,
+                                                       const float *score, int32_t eos_id, double *est)
+{
+    __shared__ double part[4];
+    const int64_t b = blockIdx.x;
+    double acc = 0.0;
+    for (int32_t i = threadIdx.x; i < N; i += 256) {
+        const int32_t *seq = tokens + (b * N + i) * T;
+        double s = 0.0;
+        for (int32_t t = 0; t < T; ++t) {
+            const int32_t tok = seq[t];
+            if (tok >= 0 && tok < V) s += (double)score[tok];
+            if (eos_id >= 0 && tok == eos_id) break;
+        }
+        acc += s;
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) est[b] = (part[0] + part[1] + part[2] + part[3]) / (double)N;
+}
+
 }  // namespace
 
 as_status launch_lattice(as_ctx *ctx, const float *u, int32_t B, int32_t N, float *codes_out,
@@ -606,6 +632,16 @@ as_status launch_lattice(as_ctx *ctx, const float *u, int32_t B, int32_t N, floa
     if (n == 0) return AS_OK;
     hipLaunchKernelGGL(lattice_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, u, B, N,
                        codes_out, prompts, prev_out, finished_out);
+    AS_HIP_TRY(ctx, hipGetLastError());
+    return AS_OK;
+}
+
+as_status launch_estimate(as_ctx *ctx, const int32_t *tokens, int32_t B, int32_t N, int32_t T, const float *score,
+                          int32_t eos_id, double *est_out)
+{
+    if (B == 0) return AS_OK;
+    hipLaunchKernelGGL(estimate_kernel, dim3((unsigned)B), dim3(256), 0, ctx->stream, tokens, N, T, ctx->V, score,
+                       eos_id, est_out);
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }

@@ -241,6 +241,18 @@ def test_shifted_lattice_sample_mean_is_unbiased():
         est = np.array([[s([int(t) for t in row]) for row in beam] for beam in toks]).mean(axis=1)
         se = est.std(ddof=1) / math.sqrt(K)
         assert abs(est.mean() - exact) < 4 * se + 1e-12, (s.__name__, est.mean(), exact, se)
+    # the oracle's own estimator routine (additive per-token scores, EOS ends the sequence): same numbers
+    # as the sums spelled out above, and the zero-variance case of Prop. 2 for a first-token indicator
+    def s_add(seq):
+        n = s_len(seq)
+        return float(sum(weights[t] for t in seq[:n]))
+    want = np.array([[s_add([int(t) for t in row]) for row in beam] for beam in toks]).mean(axis=1)
+    got = oracle.estimate_mean(toks, weights, eos_id=eos)
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+    exact = sum(p * s_add(k) for k, p in zip(keys, probs))
+    assert abs(got.mean() - exact) < 4 * got.std(ddof=1) / math.sqrt(K) + 1e-12
+    ones = oracle.estimate_mean(toks[:, :, :1], np.ones(V), eos_id=-1)
+    assert np.all(ones == 1.0)
 
 
 # --------------------------------------------------------------------------
