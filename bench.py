@@ -145,6 +145,32 @@ def main():
     if thr_n:
         out["threshold_kernel"] = {"avg_launch_us": thr_ms / thr_n * 1e3, "launches": thr_n}
 
+    # ---- the same decode without the logits round trip (no logit modifiers; logits stay fp32 on chip)
+    if top_k <= 0 and not (0.0 < top_p < 1.0) and cfg["dtype"] == "bf16" and V <= 32768:
+        tokens_f = torch.empty_like(tokens)
+        for _ in range(args.warmup):
+            B.as_decode_fused(ctx, model, prompts, N, T, u, temp, eos, tokens_f)
+        torch.cuda.synchronize()
+        f0 = time.perf_counter()
+        for _ in range(args.steps):
+            B.as_decode_fused(ctx, model, prompts, N, T, u, temp, eos, tokens_f)
+        torch.cuda.synchronize()
+        f1 = time.perf_counter()
+        ctx.profile_read(0); ctx.profile_read(1)
+        ctx.profile(True)
+        for _ in range(3):
+            B.as_decode_fused(ctx, model, prompts, N, T, u, temp, eos, tokens_f)
+        fs_ms, fs_n, _ = ctx.profile_read(0)
+        fg_ms, fg_n, _ = ctx.profile_read(1)
+        ctx.profile(False)
+        same = float((tokens_f[:, :, 0] == tokens[:, :, 0]).float().mean().item())
+        out["fused_decode"] = {
+            "what": "as_decode_fused: logits kernel leaves 8 bytes per 32 logits, sampling kernel recomputes the "
+                    "one group its code falls into",
+            "value": code_steps / (f1 - f0), "unit": "code-steps/s", "ms_per_step": (f1 - f0) / args.steps * 1e3,
+            "logits_kernel_us": fg_ms / max(fg_n, 1) * 1e3, "sampling_kernel_us": fs_ms / max(fs_n, 1) * 1e3,
+            "first_tokens_equal_to_unfused_bf16_decode": same}
+
     # ---- encode direction (sequence -> code interval) over the sequences just decoded
     lo = torch.empty(R, dtype=torch.float64, device="cuda")
     width = torch.empty(R, dtype=torch.float64, device="cuda")

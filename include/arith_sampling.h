@@ -200,6 +200,46 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts,
                     int32_t *tokens_out, float *codes_out);
 
 /*
+ * The two halves of the fused decode below, callable on their own.
+ *
+ * as_bigram_group_mass: what as_bigram_logits would give, reduced on chip to one pair
+ * per row and per group g of 32 consecutive tokens: with y_v = logit_v * log2(e)/temp,
+ *     mass_out[r, g] = ( sum over the group of 2^(y_v - ref), ref ),  ref = ceil(max y_v)
+ * (two floats; groups are in vocabulary order, so their running sums are the cumulative
+ * distribution of Sec. 3.1 sampled every 32 tokens).
+ *   prev        DEVICE int32[rows]
+ *   mass_out    DEVICE float[rows, ldp, 2], 16-byte aligned; ldp a multiple of 16,
+ *               ldp >= ceil(V/32); entries past ceil(V/32) are not written
+ *
+ * as_step_fused: one step of Algorithm 1 (Sec. 4.1) from those group masses: finds the
+ * group of each row's code, recomputes that group's 32 logits from the model (row
+ * prev[r]), finishes the bucket search and rescales the code.  Arguments as in
+ * as_step_ex; ldp <= 1024 (V <= 32768).
+ * Both need bf16 weights and a rank d that is a multiple of 64 and at least 128.
+ */
+as_status as_bigram_group_mass(as_ctx *ctx, const as_model *model, const int32_t *prev,
+                               int64_t rows, float temp, float *mass_out, int64_t ldp);
+as_status as_step_fused(as_ctx *ctx, const as_model *model, const float *mass, int64_t ldp,
+                        const int32_t *prev, int64_t rows, const float *codes, float temp,
+                        int32_t *tokens_out, float *codes_out, const uint8_t *finished_in,
+                        int32_t eos_id, uint8_t *finished_out);
+
+/*
+ * as_decode without the logits round trip (the same Algorithm 1, Sec. 4.1, over the same
+ * model): the logits kernel keeps its tile of logits on chip and leaves only, per row and
+ * per group of 32 consecutive logits, the group's softmax mass; the sampling kernel finds
+ * the group a code falls into, recomputes that group's 32 logits from the model and
+ * finishes the bucket search and the rescaling.  Logits are used as accumulated in fp32
+ * (they are never rounded to a storage type), so results agree with as_decode on an fp32
+ * context only up to the accumulation order.
+ * No logit modifiers (top_k / top_p); needs bf16 weights, a rank d that is a multiple of
+ * 64 and at least 128, V <= 32768; AS_ERR_UNSUPPORTED otherwise.  Arguments as in as_decode.
+ */
+as_status as_decode_fused(as_ctx *ctx, const as_model *model, const int32_t *prompts,
+                          int32_t B, int32_t N, int32_t T, const float *u, float temp,
+                          int32_t eos_id, int32_t *tokens_out, float *codes_out);
+
+/*
  * Ancestral sampling with the same kernels (Sec. 3.3; Sec. 3.1, last paragraph: with a
  * fresh uniform per step the bucket search is inverse-CDF categorical sampling).  As
  * as_decode, except that the code of row r at step t is uniforms[t*B*N + r] and the

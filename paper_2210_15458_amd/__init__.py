@@ -5,7 +5,7 @@ that the seeded input generators (`synth`) stay importable on their own.
 """
 
 _BINDING_NAMES = ("Ctx", "Model", "as_step", "as_step_ex", "as_lattice", "as_bigram_logits", "as_decode",
-                  "as_interval_step", "as_encode", "as_decode_ancestral", "as_estimate_mean",
+                  "as_interval_step", "as_encode", "as_decode_ancestral", "as_estimate_mean", "as_decode_fused", "as_bigram_group_mass", "as_step_fused",
                   "ArithSamplingError", "lib", "LIB_PATH", "AS_F32", "AS_BF16")
 
 

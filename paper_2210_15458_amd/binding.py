@@ -49,13 +49,17 @@ def lib():
     L.as_encode.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, f32, i32, vp, vp]
     L.as_decode_ancestral.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, f32, i32, vp]
     L.as_estimate_mean.argtypes = [vp, vp, i32, i32, i32, vp, i32, vp]
+    L.as_decode_fused.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, vp, vp]
+    L.as_bigram_group_mass.argtypes = [vp, vp, vp, i64, f32, vp, i64]
+    L.as_step_fused.argtypes = [vp, vp, vp, i64, vp, i64, vp, f32, vp, vp, vp, i32, vp]
     L.as_ctx_profile.argtypes = [vp, C.c_int]
     L.as_ctx_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(i64)]
     L.as_ctx_profile.restype = C.c_int
     L.as_ctx_profile_read.restype = C.c_int
     for name in ("as_ctx_create", "as_ctx_destroy", "as_step", "as_step_ex", "as_lattice",
                  "as_model_create_bigram", "as_model_destroy", "as_bigram_logits", "as_decode",
-                 "as_interval_step", "as_encode", "as_decode_ancestral", "as_estimate_mean"):
+                 "as_interval_step", "as_encode", "as_decode_ancestral", "as_estimate_mean", "as_decode_fused",
+                 "as_bigram_group_mass", "as_step_fused"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -235,3 +239,32 @@ def as_estimate_mean(ctx, tokens, score, eos_id, est_out):
     ctx._check(lib().as_estimate_mean(
         ctx._h, _dev(tokens, torch.int32, "tokens"), B, N, T, _dev(score, torch.float32, "score", ctx.V),
         int(eos_id), _dev(est_out, torch.float64, "est_out", B)))
+
+
+def as_decode_fused(ctx, model, prompts, N, T, u, temp, eos_id, tokens_out, codes_out=None):
+    B = prompts.numel()
+    ctx._check(lib().as_decode_fused(
+        ctx._h, model._h, _dev(prompts, torch.int32, "prompts"), B, int(N), int(T),
+        _dev(u, torch.float32, "u", B), float(temp), int(eos_id),
+        _dev(tokens_out, torch.int32, "tokens_out", B * int(N) * int(T)),
+        _dev(codes_out, torch.float32, "codes_out", B * int(N))))
+
+
+def as_bigram_group_mass(ctx, model, prev, temp, mass_out):
+    if mass_out.dim() != 3 or mass_out.shape[2] != 2:
+        raise ValueError("mass_out must be [rows, ldp, 2]")
+    rows, ldp = mass_out.shape[0], mass_out.shape[1]
+    ctx._check(lib().as_bigram_group_mass(ctx._h, model._h, _dev(prev, torch.int32, "prev", rows), rows, float(temp),
+                                          _dev(mass_out, torch.float32, "mass_out"), ldp))
+
+
+def as_step_fused(ctx, model, mass, prev, codes, temp, tokens_out, codes_out, finished_in=None, eos_id=-1,
+                  finished_out=None):
+    if mass.dim() != 3 or mass.shape[2] != 2:
+        raise ValueError("mass must be [rows, ldp, 2]")
+    rows, ldp = mass.shape[0], mass.shape[1]
+    ctx._check(lib().as_step_fused(
+        ctx._h, model._h, _dev(mass, torch.float32, "mass"), ldp, _dev(prev, torch.int32, "prev", rows), rows,
+        _dev(codes, torch.float32, "codes", rows), float(temp), _dev(tokens_out, torch.int32, "tokens_out", rows),
+        _dev(codes_out, torch.float32, "codes_out", rows), _dev(finished_in, torch.uint8, "finished_in", rows),
+        int(eos_id), _dev(finished_out, torch.uint8, "finished_out", rows)))

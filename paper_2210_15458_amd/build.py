@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libarith_sampling.so")
-SOURCES = ["as_api.hip", "as_step.hip", "as_threshold.hip", "as_model.hip", "as_interval.hip"]
+SOURCES = ["as_api.hip", "as_step.hip", "as_threshold.hip", "as_model.hip", "as_interval.hip", "as_fused.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -343,6 +343,108 @@ as_status as_decode_ancestral(as_ctx *ctx, const as_model *model, const int32_t 
                        nullptr);
 }
 
+as_status as_bigram_group_mass(as_ctx *ctx, const as_model *model, const int32_t *prev, int64_t rows, float temp,
+                               float *mass_out, int64_t ldp)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (!model) return fail(ctx, AS_ERR_INVALID_ARG, "model is NULL");
+    if (model->V != ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "model and context disagree on V");
+    if (rows < 0 || rows > ctx->max_rows) return fail(ctx, AS_ERR_INVALID_ARG, "rows outside [0, max_rows]");
+    if (rows == 0) return AS_OK;
+    if (!prev || !mass_out) return fail(ctx, AS_ERR_INVALID_ARG, "prev and mass_out must not be NULL");
+    if (!(temp > 0.f) || !isfinite(temp)) return fail(ctx, AS_ERR_INVALID_ARG, "temp must be finite and > 0");
+    const int64_t ngroups = ((int64_t)ctx->V + 31) / 32;
+    if (ldp < ngroups || ldp % 16 != 0 || reinterpret_cast<uintptr_t>(mass_out) % 16 != 0)
+        return fail(ctx, AS_ERR_INVALID_ARG, "ldp must be a multiple of 16 covering ceil(V/32) groups, mass_out 16-byte aligned");
+    if (!fused_path_applies(ctx, model))
+        return fail(ctx, AS_ERR_UNSUPPORTED,
+                    "group masses need bf16 weights, a rank that is a multiple of 64 and at least 128, "
+                    "and operands below 4 GB");
+    return launch_bigram_partials(ctx, model, prev, rows, temp, reinterpret_cast<float2 *>(mass_out), ldp);
+}
+
+as_status as_step_fused(as_ctx *ctx, const as_model *model, const float *mass, int64_t ldp, const int32_t *prev,
+                        int64_t rows, const float *codes, float temp, int32_t *tokens_out, float *codes_out,
+                        const uint8_t *finished_in, int32_t eos_id, uint8_t *finished_out)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (!model) return fail(ctx, AS_ERR_INVALID_ARG, "model is NULL");
+    if (model->V != ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "model and context disagree on V");
+    if (rows < 0 || rows > ctx->max_rows) return fail(ctx, AS_ERR_INVALID_ARG, "rows outside [0, max_rows]");
+    if (rows == 0) return AS_OK;
+    if (!mass || !prev || !codes || !tokens_out || !codes_out)
+        return fail(ctx, AS_ERR_INVALID_ARG, "mass, prev, codes, tokens_out and codes_out must not be NULL");
+    if (!(temp > 0.f) || !isfinite(temp)) return fail(ctx, AS_ERR_INVALID_ARG, "temp must be finite and > 0");
+    if (finished_in && eos_id < 0) return fail(ctx, AS_ERR_INVALID_ARG, "finished_in given without an eos_id to emit");
+    if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
+    const int64_t ngroups = ((int64_t)ctx->V + 31) / 32;
+    if (ldp < ngroups || ldp % 16 != 0 || ldp > 64 * 16 || reinterpret_cast<uintptr_t>(mass) % 16 != 0)
+        return fail(ctx, AS_ERR_INVALID_ARG,
+                    "ldp must be a multiple of 16, at most 1024, covering ceil(V/32) groups; mass 16-byte aligned");
+    if (!fused_path_applies(ctx, model))
+        return fail(ctx, AS_ERR_UNSUPPORTED, "the fused step needs bf16 weights and a rank that is a multiple of 64");
+    FusedArgs a{};
+    a.part = reinterpret_cast<const float2 *>(mass); a.ldp = ldp; a.ngroups = (int32_t)ngroups; a.rows = rows;
+    a.V = ctx->V; a.d = model->d;
+    a.E = static_cast<const uint16_t *>(model->E); a.Ut = static_cast<const uint16_t *>(model->Ut);
+    a.alpha = (float)((double)model->scale / sqrt((double)model->d) * 1.44269504088896340736 / (double)temp);
+    a.codes = codes; a.codes_out = codes_out; a.tokens_out = tokens_out; a.tok_stride = 1;
+    a.finished_in = finished_in; a.eos_id = eos_id; a.finished_out = finished_out; a.prev = prev; a.prev_out = nullptr;
+    return launch_fused_sample(ctx, a);
+}
+
+as_status as_decode_fused(as_ctx *ctx, const as_model *model, const int32_t *prompts, int32_t B, int32_t N, int32_t T,
+                          const float *u, float temp, int32_t eos_id, int32_t *tokens_out, float *codes_out)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (!model) return fail(ctx, AS_ERR_INVALID_ARG, "model is NULL");
+    if (model->V != ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "model and context disagree on V");
+    if (B < 0 || N < 1 || T < 0) return fail(ctx, AS_ERR_INVALID_ARG, "B, T must be >= 0 and N >= 1");
+    const int64_t R = (int64_t)B * N;
+    if (R > ctx->max_rows) return fail(ctx, AS_ERR_INVALID_ARG, "B*N exceeds max_rows");
+    if (R == 0) return AS_OK;
+    if (!prompts || !u) return fail(ctx, AS_ERR_INVALID_ARG, "prompts and u must not be NULL");
+    if (T > 0 && !tokens_out) return fail(ctx, AS_ERR_INVALID_ARG, "tokens_out must not be NULL");
+    if (!(temp > 0.f) || !isfinite(temp)) return fail(ctx, AS_ERR_INVALID_ARG, "temp must be finite and > 0");
+    if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
+    if (!fused_path_applies(ctx, model))
+        return fail(ctx, AS_ERR_UNSUPPORTED,
+                    "the fused decode needs bf16 weights, a rank that is a multiple of 64 and at least 128, "
+                    "and operands below 4 GB");
+
+    const int32_t ngroups = (ctx->V + 31) / 32;
+    const int64_t ldp = ((int64_t)ngroups + 15) / 16 * 16;
+    if (ldp > 64 * 16) return fail(ctx, AS_ERR_UNSUPPORTED, "the fused decode takes vocabularies up to 32768");
+    as_status st = grow(ctx, ctx->logits, (size_t)R * ldp * sizeof(float2));
+    if (st != AS_OK) return st;
+    st = grow(ctx, ctx->state, (size_t)R * 9);
+    if (st != AS_OK) return st;
+    float *codes = static_cast<float *>(ctx->state.ptr);
+    int32_t *prev = reinterpret_cast<int32_t *>(codes + R);
+    uint8_t *fin = reinterpret_cast<uint8_t *>(prev + R);
+    float2 *part = static_cast<float2 *>(ctx->logits.ptr);
+
+    st = launch_lattice(ctx, u, B, N, codes, prompts, prev, fin);
+    if (st != AS_OK) return st;
+    for (int32_t t = 0; t < T; ++t) {
+        st = launch_bigram_partials(ctx, model, prev, R, temp, part, ldp);
+        if (st != AS_OK) return st;
+        FusedArgs a{};
+        a.part = part; a.ldp = ldp; a.ngroups = ngroups; a.rows = R; a.V = ctx->V; a.d = model->d;
+        a.E = static_cast<const uint16_t *>(model->E); a.Ut = static_cast<const uint16_t *>(model->Ut);
+        a.alpha = (float)((double)model->scale / sqrt((double)model->d) * 1.44269504088896340736 / (double)temp);
+        a.codes = codes; a.codes_out = codes; a.tokens_out = tokens_out + t; a.tok_stride = T;
+        a.finished_in = eos_id >= 0 ? fin : nullptr; a.eos_id = eos_id;
+        a.finished_out = eos_id >= 0 ? fin : nullptr; a.prev = prev; a.prev_out = prev;
+        st = launch_fused_sample(ctx, a);
+        if (st != AS_OK) return st;
+    }
+    if (codes_out)
+        AS_HIP_TRY(ctx, hipMemcpyAsync(codes_out, codes, (size_t)R * sizeof(float), hipMemcpyDeviceToDevice,
+                                       ctx->stream));
+    return AS_OK;
+}
+
 as_status as_estimate_mean(as_ctx *ctx, const int32_t *tokens, int32_t B, int32_t N, int32_t T, const float *score,
                            int32_t eos_id, double *est_out)
 {

@@ -137,7 +137,32 @@ struct IntervalArgs {
     int32_t *prev_out;           // encode state: next step's conditioning token, or null
 };
 
+struct FusedArgs {
+    const float2 *part;          // [rows, ldp]: (sum, reference) per group of 32 logits
+    int64_t ldp;                 // multiple of 16
+    int32_t ngroups;             // ceil(V / 32)
+    int64_t rows;
+    int32_t V;
+    int32_t d;
+    const uint16_t *E;           // [V, d] bf16
+    const uint16_t *Ut;          // [V, d] bf16
+    float alpha;                 // scale/sqrt(d) * log2(e)/temp
+    const float *codes;
+    float *codes_out;
+    int32_t *tokens_out;
+    int64_t tok_stride;
+    const uint8_t *finished_in;
+    int32_t eos_id;
+    uint8_t *finished_out;
+    const int32_t *prev;         // conditioning token of each row (may alias prev_out)
+    int32_t *prev_out;
+};
+
 as_status launch_step(as_ctx *ctx, const StepArgs &a);
+as_status launch_fused_sample(as_ctx *ctx, const FusedArgs &a);
+as_status launch_bigram_partials(as_ctx *ctx, const as_model *m, const int32_t *prev, int64_t rows, float temp,
+                                 float2 *part, int64_t ldp);
+bool fused_path_applies(const as_ctx *ctx, const as_model *m);
 as_status launch_interval(as_ctx *ctx, const IntervalArgs &a);
 as_status launch_interval_init(as_ctx *ctx, int32_t B, int32_t N, const int32_t *prompts, double *lo,
                                double *width, int32_t *prev, uint8_t *finished);

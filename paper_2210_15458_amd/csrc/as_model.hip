@@ -107,7 +107,11 @@ __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
     return r;
 }
 
-template <class OutT>
+// FUSED: instead of the logits, write per row and per group of 32 consecutive logits the pair
+// (sum of exp2(y - ref), ref) with y = logit * log2(e)/temp and ref = ceil(max y) -- what the sampling
+// step needs to find the group its code falls into (the logits never reach memory).  C then is that table,
+// float2 [R, ldc], and alpha carries the extra factor log2(e)/temp.
+template <class OutT, bool FUSED = false>
 __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t *__restrict__ E,
                                                                  const uint16_t *__restrict__ Ut,
                                                                  const int32_t *__restrict__ prev, int64_t R,
@@ -324,7 +328,48 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
         // ---- epilogue: scale, round once to the storage type, transpose through this wave's 32 x 128 B of
         // staging (16-byte pieces permuted by the row's bits 1..3), write 128-byte row pieces.  The LDS
         // accesses are written by hand so that the compiler does not tie them to the loads in flight.
-        {
+        if constexpr (FUSED) {
+            // Lane l holds, for each 32-row group i and each 32-column MFMA tile j, 16 logits of batch row
+            // l%32: columns 8q + 4*(l/32) + 0..3, q = 0..3; the other 16 of that row and tile sit in lane l^32.
+            const int b = lane & 31, h = lane >> 5;
+            float2 *P = reinterpret_cast<float2 *>(C);
+            if (n0 + PN > V) {                    // last column tile: columns past V carry no mass
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int jx = 0; jx < 4; ++jx)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int64_t n = n0 + wn * 128 + jx * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                            if (n >= V) acc[i][jx][v] = -__builtin_inff();
+                        }
+            }
+            // references of the 8 groups first (alpha > 0: the maximum commutes with the scaling), then the sums
+            float ref[2][4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int jx = 0; jx < 4; ++jx) {
+                    float mx = acc[i][jx][0];
+#pragma unroll
+                    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, acc[i][jx][v]);
+                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                    ref[i][jx] = fmaxf(ceilf(mx * alpha), -100000.f);
+                }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int jx = 0; jx < 4; ++jx) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[i][jx][v], alpha, -ref[i][jx]));
+                    sum += __shfl_xor(sum, 32, 64);
+                    const int64_t ncol = n0 + wn * 128 + jx * 32;
+                    const int64_t m = m0 + wm * 64 + i * 32 + b;
+                    if (h == 0 && m < R && ncol < V) P[m * ldc + (ncol >> 5)] = float2{sum, ref[i][jx]};
+                }
+            stores_behind = -1;      // few small stores: the next tile's first barrier simply waits for them
+        } else {
             constexpr int kPerPiece = 16 / (int)sizeof(OutT);     // outputs per 16-byte piece
             constexpr int kCols = 8 * kPerPiece;                  // tile columns per pass: 64 (bf16) or 32 (fp32)
             constexpr int kPasses = 128 / kCols;                  // per 32-row group of the wave tile
@@ -708,6 +753,27 @@ as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *pr
             else launch_dot<float, float>(ctx, m, prev, rows, logits_out, ld, alpha);
         }
     }
+    AS_HIP_TRY(ctx, hipGetLastError());
+    return AS_OK;
+}
+
+// The fused decode needs the persistent kernel (bf16 weights, rank a multiple of 64 and at least 128,
+// operands within 4 GB, 16-byte aligned).
+bool fused_path_applies(const as_ctx *ctx, const as_model *m)
+{
+    return m->wdtype == AS_BF16 && m->d % PK == 0 && m->d >= 2 * PK && (int64_t)m->V * m->d * 2 < (1LL << 32) &&
+           reinterpret_cast<uintptr_t>(m->E) % 16 == 0 && reinterpret_cast<uintptr_t>(m->Ut) % 16 == 0 &&
+           ctx->num_cus >= 8;
+}
+
+as_status launch_bigram_partials(as_ctx *ctx, const as_model *m, const int32_t *prev, int64_t rows, float temp,
+                                 float2 *part, int64_t ldp)
+{
+    if (rows == 0) return AS_OK;
+    const float alpha = (float)((double)m->scale / sqrt((double)m->d) * 1.44269504088896340736 / (double)temp);
+    const dim3 grid((unsigned)(8 * (ctx->num_cus / 8))), block(512);
+    launch(ctx, kKernelLogits, bigram_gemm_persistent<float, true>, grid, block, 0, (const uint16_t *)m->E,
+           (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha, reinterpret_cast<float *>(part), ldp, 0);
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }
