@@ -13,6 +13,9 @@ Prints ONE JSON line: whole-job code-steps/s, plus
                 taken from the dispatch's own HIP events during the timed region
   roofline_cold the same kernel launched alone over >1 GiB of rotating logits
                 buffers, so no row can be served from the 256 MB Infinity Cache
+  roofline_16x_rows  the same kernel, one launch over 16x the rows (1 GiB)
+  fused_decode  the decode without the logits round trip (as_decode_fused)
+  encode        the encode direction over the decoded sequences (as_encode)
   logits_gemm   the MFMA logits kernel: achieved TFLOP/s against the bf16 peak
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on a bounded
                 sample of the same workload
@@ -246,6 +249,37 @@ def main():
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
             "avg_launch_us": us, "launches": n, "code_steps_per_s": R / (us * 1e-6)}
         del bufs
+
+    # ---- the same kernel where a launch is long enough to amortise its fixed costs: 16x the rows, one launch
+    # over a 1 GiB logits buffer (nothing of it fits the Infinity Cache by the time it is read again)
+    if not args.no_cold and args.config == 1:
+        Rl = 16 * R
+        ld = (V + 7) // 8 * 8
+        ctxl = B.Ctx(Rl, V, tdt)
+        big = torch.empty((Rl, ld), dtype=tdt, device="cuda")
+        prevl = ((prompts.repeat_interleave(N).repeat(16) + 131 * torch.arange(Rl, device="cuda", dtype=torch.int32))
+                 % V).to(torch.int32).contiguous()
+        B.as_bigram_logits(ctxl, model, prevl, big)
+        codesl = up(synth.uniform_codes(Rl, seed=5))
+        tokl = torch.empty(Rl, dtype=torch.int32, device="cuda")
+        coutl = torch.empty(Rl, dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            B.as_step(ctxl, big, codesl, temp, top_k, top_p, tokl, coutl)
+        torch.cuda.synchronize()
+        ctxl.profile_read(0)
+        ctxl.profile(True)
+        for _ in range(20):
+            B.as_step(ctxl, big, codesl, temp, top_k, top_p, tokl, coutl)
+        ms, n, _ = ctxl.profile_read(0)
+        ctxl.profile(False)
+        us = ms / n * 1e3
+        ach = Rl * bytes_per_row / (us * 1e-6) / 1e9
+        out["roofline_16x_rows"] = {
+            "kernel": "step_kernel alone, one launch over %d rows (%.2f GiB of logits)" % (Rl, Rl * ld * esz / 2 ** 30),
+            "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "avg_launch_us": us, "launches": n, "code_steps_per_s": Rl / (us * 1e-6)}
+        del big
+        ctxl.close()
 
     # ---- CPU oracle on a bounded sample of the same workload (reported, not a target)
     if not args.no_cpu:
