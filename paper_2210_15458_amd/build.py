@@ -27,7 +27,7 @@ def stale():
     if not os.path.exists(OUT):
         return True
     t = os.path.getmtime(OUT)
-    deps = sources() + [os.path.join(CSRC, "as_common.hpp"),
+    deps = sources() + [os.path.join(CSRC, "as_common.hpp"), os.path.join(CSRC, "as_row.hpp"),
                         os.path.join(HERE, "..", "include", "arith_sampling.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 

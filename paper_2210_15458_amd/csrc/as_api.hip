@@ -186,18 +186,19 @@ as_status as_step_ex(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, 
     if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
     if (isnan(top_p)) return fail(ctx, AS_ERR_INVALID_ARG, "top_p is NaN");
 
-    const float *thr = nullptr;
-    if (truncation_on(ctx->V, top_k, top_p)) {
-        st = launch_threshold(ctx, logits, rows, ld, finished_in, row_ids, temp, top_k, top_p, ctx->thr);
-        if (st != AS_OK) return st;
-        thr = ctx->thr;
-    }
     StepArgs a{};
     a.logits = logits; a.rows = rows; a.ld = ld; a.V = ctx->V; a.dtype = ctx->dtype;
-    a.codes = codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = thr;
+    a.codes = codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = nullptr;
     a.tokens_out = tokens_out; a.tok_stride = 1; a.codes_out = codes_out;
     a.finished_in = finished_in; a.eos_id = eos_id; a.finished_out = finished_out;
     a.prob_out = prob_out; a.flo_out = flo_out; a.row_ids = row_ids; a.prev_out = nullptr;
+    if (truncation_on(ctx->V, top_k, top_p)) {
+        // top-k rows that fit the resident kernel are finished there; otherwise threshold, then step
+        if (launch_topk_step(ctx, a, top_k, top_p, &st)) return st;
+        st = launch_threshold(ctx, logits, rows, ld, finished_in, row_ids, temp, top_k, top_p, ctx->thr);
+        if (st != AS_OK) return st;
+        a.thr = ctx->thr;
+    }
     return launch_step(ctx, a);
 }
 
@@ -304,18 +305,23 @@ static as_status decode_impl(as_ctx *ctx, const as_model *model, const int32_t *
     for (int32_t t = 0; t < T; ++t) {
         st = launch_bigram_logits(ctx, model, prev, R, ctx->logits.ptr, ldw);
         if (st != AS_OK) return st;
-        if (trunc) {
-            st = launch_threshold(ctx, ctx->logits.ptr, R, ldw, eos_id >= 0 ? fin : nullptr, nullptr, temp,
-                                  top_k, top_p, ctx->thr);
-            if (st != AS_OK) return st;
-        }
         StepArgs a{};
         a.logits = ctx->logits.ptr; a.rows = R; a.ld = ldw; a.V = ctx->V; a.dtype = ctx->dtype;
-        a.codes = uniforms ? uniforms + (int64_t)t * R : codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = trunc ? ctx->thr : nullptr;
+        a.codes = uniforms ? uniforms + (int64_t)t * R : codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = nullptr;
         a.tokens_out = tokens_out + t; a.tok_stride = T; a.codes_out = codes;
         a.finished_in = eos_id >= 0 ? fin : nullptr; a.eos_id = eos_id;
         a.finished_out = eos_id >= 0 ? fin : nullptr;
         a.prob_out = nullptr; a.flo_out = nullptr; a.row_ids = nullptr; a.prev_out = prev;
+        if (trunc) {
+            if (launch_topk_step(ctx, a, top_k, top_p, &st)) {
+                if (st != AS_OK) return st;
+                continue;
+            }
+            st = launch_threshold(ctx, ctx->logits.ptr, R, ldw, eos_id >= 0 ? fin : nullptr, nullptr, temp,
+                                  top_k, top_p, ctx->thr);
+            if (st != AS_OK) return st;
+            a.thr = ctx->thr;
+        }
         st = launch_step(ctx, a);
         if (st != AS_OK) return st;
     }

@@ -166,6 +166,7 @@ bool fused_path_applies(const as_ctx *ctx, const as_model *m);
 as_status launch_interval(as_ctx *ctx, const IntervalArgs &a);
 as_status launch_interval_init(as_ctx *ctx, int32_t B, int32_t N, const int32_t *prompts, double *lo,
                                double *width, int32_t *prev, uint8_t *finished);
+bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p, as_status *st);
 as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
                            const uint8_t *finished_in, const int32_t *row_ids,
                            float temp, int32_t top_k, float top_p, float *thr_out);

@@ -42,6 +42,7 @@
 #include <utility>
 
 #include "as_common.hpp"
+#include "as_row.hpp"
 
 #ifndef AS_STEP_AHEAD
 #define AS_STEP_AHEAD 4
@@ -53,7 +54,6 @@
 namespace as {
 namespace {
 
-constexpr float kRefFloor = -100000.f;  // reference when only -inf has been seen
 constexpr float kMinShift = -300.f;     // 2^-300 is 0 in fp32: clamp before float->int
 
 template <int DT> struct Elem;
@@ -90,10 +90,6 @@ template <int DT> __device__ __forceinline__ float widen(typename Elem<DT>::T h)
     if constexpr (DT == AS_BF16) return bits_f32((uint32_t)h << 16);
     else return h;
 }
-
-// exp2 straight on the hardware instruction (no denormal fix-up: results below
-// 2^-126 may flush to zero, which is far below anything that can matter here)
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Three-operand maximum as one instruction.  (fmaxf on values that come from
 // bit casts makes the compiler quiet possible signalling NaNs first, one extra
@@ -152,41 +148,6 @@ __device__ __forceinline__ int pick_first(const double *t, double tau, double &r
 struct SumRef {
     float sum, ref;      // a sum of weights and the integer reference it is relative to
 };
-
-struct RowOut {
-    int32_t token;
-    float c_next, prob, f_lo;
-};
-
-__device__ __forceinline__ void write_row(const StepArgs &a, int64_t r, const RowOut &o)
-{
-    a.tokens_out[r * a.tok_stride] = o.token;
-    a.codes_out[r] = o.c_next;
-    if (a.finished_out) a.finished_out[r] = (a.eos_id >= 0 && o.token == a.eos_id) ? 1 : 0;
-    if (a.prob_out) a.prob_out[r] = o.prob;
-    if (a.flo_out) a.flo_out[r] = o.f_lo;
-    if (a.prev_out) a.prev_out[r] = o.token;
-}
-
-// finished sequence: padding after EOS (Sec. 3.3); the code stops moving
-__device__ __forceinline__ void write_finished(const StepArgs &a, int64_t r)
-{
-    a.tokens_out[r * a.tok_stride] = a.eos_id;
-    a.codes_out[r] = a.codes[r];
-    if (a.finished_out) a.finished_out[r] = 1;
-    if (a.prob_out) a.prob_out[r] = 1.f;
-    if (a.flo_out) a.flo_out[r] = 0.f;
-    if (a.prev_out) a.prev_out[r] = a.eos_id;
-}
-
-// c' = (c*S - before)/e_v: the difference is taken in fp64, the quotient is an fp32 result anyway
-__device__ __forceinline__ float rescale_code(double tau, double before, double ev)
-{
-    float cnf = (float)(tau - before) / (float)ev;
-    cnf = fminf(cnf, 0x1.fffffep-1f);        // 1 - 2^-24
-    if (!(cnf >= 0.f)) cnf = 0.f;
-    return cnf;
-}
 
 // ===========================================================================
 // fast kernel: rows start on 16 bytes and hold a whole number of vectors
@@ -521,80 +482,15 @@ template <int DT, bool HAS_THR>
 __global__ __launch_bounds__(256) void step_generic_kernel(StepArgs a)
 {
     using T = typename Elem<DT>::T;
-    __shared__ float s_red[4];
-    __shared__ double s_tot[256];
-    __shared__ int s_hit;
-    __shared__ double s_run;
-
+    __shared__ GenericScratch sh;
     const int64_t r = blockIdx.x;
-    const int tid = threadIdx.x;
     if (a.finished_in != nullptr && a.finished_in[r] != 0) {
-        if (tid == 0) write_finished(a, r);
+        if (threadIdx.x == 0) write_finished(a, r);
         return;
     }
-    const int64_t src = a.row_ids ? (int64_t)a.row_ids[r] : r;
-    const T *row = reinterpret_cast<const T *>(a.logits) + src * a.ld;
-    const int32_t V = a.V;
-    const float k = a.k;
     float thr = -__builtin_inff();
     if constexpr (HAS_THR) thr = a.thr[r];
-    const int32_t len = (V + 255) / 256;
-    const int32_t lo = tid * len, hi = (lo + len < V) ? lo + len : V;
-
-    float m = -__builtin_inff();
-    for (int32_t v = lo; v < hi; ++v) {
-        const float x = widen<DT>(row[v]);
-        if (x >= thr) m = fmaxf(m, x);
-    }
-    m = wave_max(m);
-    if ((tid & 63) == 0) s_red[tid >> 6] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-    const float ref = fmaxf(ceilf(m * k), kRefFloor);
-
-    double tot = 0.0;
-    for (int32_t v = lo; v < hi; ++v) {
-        const float x = widen<DT>(row[v]);
-        if (x >= thr) tot += (double)fast_exp2(fmaf(x, k, -ref));
-    }
-    s_tot[tid] = tot;
-    __syncthreads();
-    if (tid == 0) {
-        double S = 0.0;
-        for (int i = 0; i < 256; ++i) S += s_tot[i];
-        const double tau = (double)a.codes[r] * S;
-        double run = 0.0, run_last = 0.0;
-        int hit = -1, last_nz = 0;
-        for (int i = 0; i < 256; ++i) {
-            if (s_tot[i] > 0.0) { last_nz = i; run_last = run; }
-            if (run + s_tot[i] > tau) { hit = i; break; }
-            run += s_tot[i];
-        }
-        if (hit < 0) { hit = last_nz; run = run_last; }
-        s_hit = hit;
-        s_run = run;
-        s_tot[0] = S;                      // thread 0's own total is not needed any more
-    }
-    __syncthreads();
-    if (tid != s_hit) return;
-    const double S = s_tot[0];
-    const double tau = (double)a.codes[r] * S;
-    double acc = s_run, before = s_run, before_last = s_run, ev = 0.0, ev_last = 0.0;
-    int32_t tok = -1, tok_last = lo < V ? lo : V - 1;
-    for (int32_t v = lo; v < hi; ++v) {
-        const float x = widen<DT>(row[v]);
-        const double e = (x >= thr) ? (double)fast_exp2(fmaf(x, k, -ref)) : 0.0;
-        if (e > 0.0) { tok_last = v; before_last = acc; ev_last = e; }
-        if (tok < 0 && acc + e > tau) { tok = v; before = acc; ev = e; }
-        acc += e;
-    }
-    if (tok < 0) { tok = tok_last; before = before_last; ev = ev_last; }
-    RowOut o;
-    o.token = tok;
-    o.c_next = rescale_code(tau, before, ev);
-    o.prob = (float)(ev / S);
-    o.f_lo = (float)(before / S);
-    write_row(a, r, o);
+    generic_step_row<T>(a, r, thr, sh);
 }
 
 // ---------------------------------------------------------------------------

@@ -24,6 +24,7 @@
 #include <type_traits>
 
 #include "as_common.hpp"
+#include "as_row.hpp"
 
 namespace as {
 namespace {
@@ -262,6 +263,7 @@ struct Resident {
     unsigned long long hist[kCoarseBins];
     uint32_t ckey[kCandCap];
     uint32_t cq[kCandCap];
+    uint32_t cidx[kCandCap];             // vocabulary index of each candidate (fused step)
     uint32_t mcount[kThreads];           // thread maxima per coarse bin (top-k)
     unsigned long long wave_tot[kThreads / 64];
     uint32_t ncand;
@@ -273,6 +275,7 @@ struct Resident {
 union Scratch {
     Shared radix;
     Resident res;
+    GenericScratch gen;
 };
 
 __device__ __forceinline__ uint32_t wave_reduce_umax(uint32_t x)
@@ -301,12 +304,16 @@ __device__ __forceinline__ int coarse_bin(float y)
     return (int)b;
 }
 
-template <int DT, bool HAS_K, bool HAS_P>
+// STEP (with HAS_K): go on and finish the sampling step for the row from the candidate table -- after top-k
+// every kept logit is in it, so the row is not read a second time.  sa then carries the step's arguments.
+template <int DT, bool HAS_K, bool HAS_P, bool STEP = false>
 __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void *logits, int64_t ld, int32_t V,
                                                                       const uint8_t *finished_in,
                                                                       const int32_t *row_ids, float temp,
-                                                                      int32_t top_k, float top_p, float *thr_out)
+                                                                      int32_t top_k, float top_p, float *thr_out,
+                                                                      StepArgs sa)
 {
+    static_assert(!STEP || HAS_K, "the fused step works on the top-k candidate table");
     using K = Key<DT>;
     using T = typename K::T;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -318,7 +325,12 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
 
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
-    if (finished_in != nullptr && finished_in[r] != 0) return;
+    if (finished_in != nullptr && finished_in[r] != 0) {
+        if constexpr (STEP) {
+            if (tid == 0) write_finished(sa, r);
+        }
+        return;
+    }
     const int64_t src = row_ids ? (int64_t)row_ids[r] : r;
     const T *row = reinterpret_cast<const T *>(logits) + src * ld;
 
@@ -448,23 +460,27 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
         __syncthreads();
         const uint32_t lkey = sh.lkey;
         forget_row();
-        auto candidate = [&](uint32_t key) __attribute__((always_inline)) {
+        auto candidate = [&](uint32_t key, int32_t v) __attribute__((always_inline)) {
             const uint32_t i = atomicAdd(&sh.ncand, 1u);
-            if (i < (uint32_t)kCandCap) sh.ckey[i] = key;
+            if (i < (uint32_t)kCandCap) {
+                sh.ckey[i] = key;
+                if constexpr (STEP) sh.cidx[i] = (uint32_t)v;
+            }
         };
 #pragma unroll
         for (int p = 0; p < NP; ++p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t w = pc[p][i];
+                const int32_t v0 = (p * kThreads + tid) * EPP;
                 if constexpr (kHalf) {
                     const uint32_t t = lkey << 16;
                     if (w >= t || (w << 16) >= t) {          // rare
-                        if ((w >> 16) >= lkey) candidate(w >> 16);
-                        if ((w & 0xffffu) >= lkey) candidate(w & 0xffffu);
+                        if ((w >> 16) >= lkey) candidate(w >> 16, v0 + 2 * i + 1);
+                        if ((w & 0xffffu) >= lkey) candidate(w & 0xffffu, v0 + 2 * i);
                     }
                 } else {
-                    if (w >= lkey) candidate(w);
+                    if (w >= lkey) candidate(w, v0 + i);
                 }
             }
         __syncthreads();
@@ -648,7 +664,75 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
         __syncthreads();
         thr_key = radix_threshold<DT>(sc.radix, row, V, temp, top_k, top_p);
     }
-    if (tid == 0) thr_out[r] = K::from_key(thr_key);
+    if (tid == 0 && thr_out != nullptr) thr_out[r] = K::from_key(thr_key);
+
+    if constexpr (STEP) {
+        __syncthreads();
+        if (fall) {
+            generic_step_row<T>(sa, r, K::from_key(thr_key), sc.gen);
+            return;
+        }
+        // ---- the sampling step on the kept candidates (Sec. 4.1 loop body): weights against an integer
+        // reference, cumulative sums in vocabulary order, first bucket above the code, rescale
+        const float k = sa.k;
+        float m = -__builtin_inff();
+        for (uint32_t c = tid; c < ncand; c += kThreads)
+            if (sh.ckey[c] >= thr_key) m = fmaxf(m, K::from_key(sh.ckey[c]));
+        m = wave_max(m);
+        float *fred = reinterpret_cast<float *>(sh.hist);
+        double *dred = reinterpret_cast<double *>(sh.hist) + 8;
+        if ((tid & 63) == 0) fred[tid >> 6] = m;
+        if (tid == 0) sh.pick = 0xffffffffu;
+        __syncthreads();
+        m = fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]));
+        const float ref = fmaxf(ceilf(m * k), kRefFloor);
+        double part = 0.0;
+        for (uint32_t c = tid; c < ncand; c += kThreads) {
+            const uint32_t key = sh.ckey[c];
+            const float e = key >= thr_key ? fast_exp2(fmaf(K::from_key(key), k, -ref)) : 0.f;
+            sh.cq[c] = __builtin_bit_cast(uint32_t, e);
+            part += (double)e;
+        }
+        part = wave_sum(part);
+        if ((tid & 63) == 0) dred[tid >> 6] = part;
+        __syncthreads();
+        const double S = (dred[0] + dred[1]) + (dred[2] + dred[3]);
+        const double tau = (double)sa.codes[r] * S;
+        for (uint32_t c = tid; c < ncand; c += kThreads) {
+            const float e = __builtin_bit_cast(float, sh.cq[c]);
+            if (!(e > 0.f)) continue;
+            const uint32_t my = sh.cidx[c];
+            double lo = 0.0;
+            for (uint32_t j = 0; j < ncand; ++j)
+                lo += sh.cidx[j] < my ? (double)__builtin_bit_cast(float, sh.cq[j]) : 0.0;
+            if (lo <= tau && tau < lo + (double)e) {
+                sh.pick = c;
+                dred[4] = lo;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t win = sh.pick;
+            double lo = dred[4];
+            if (win == 0xffffffffu) {
+                // code at the very top by rounding: the last kept token of the vocabulary
+                uint32_t best = 0;
+                win = 0;
+                for (uint32_t j = 0; j < ncand; ++j)
+                    if (__builtin_bit_cast(float, sh.cq[j]) > 0.f && sh.cidx[j] >= best) { best = sh.cidx[j]; win = j; }
+                lo = 0.0;
+                for (uint32_t j = 0; j < ncand; ++j)
+                    lo += sh.cidx[j] < best ? (double)__builtin_bit_cast(float, sh.cq[j]) : 0.0;
+            }
+            const double ev = (double)__builtin_bit_cast(float, sh.cq[win]);
+            RowOut o;
+            o.token = (int32_t)sh.cidx[win];
+            o.c_next = rescale_code(tau, lo, ev);
+            o.prob = (float)(ev / S);
+            o.f_lo = (float)(lo / S);
+            write_row(sa, r, o);
+        }
+    }
 }
 
 }  // namespace
@@ -661,13 +745,45 @@ void launch_resident(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, 
     const dim3 grid((unsigned)rows), block(kThreads);
     if (has_k && has_p)
         launch(ctx, kKernelThreshold, threshold_resident_kernel<DT, true, true>, grid, block, 0, logits, ld, ctx->V,
-               finished_in, row_ids, temp, top_k, top_p, thr_out);
+               finished_in, row_ids, temp, top_k, top_p, thr_out, StepArgs{});
     else if (has_k)
         launch(ctx, kKernelThreshold, threshold_resident_kernel<DT, true, false>, grid, block, 0, logits, ld, ctx->V,
-               finished_in, row_ids, temp, top_k, top_p, thr_out);
+               finished_in, row_ids, temp, top_k, top_p, thr_out, StepArgs{});
     else
         launch(ctx, kKernelThreshold, threshold_resident_kernel<DT, false, true>, grid, block, 0, logits, ld, ctx->V,
-               finished_in, row_ids, temp, top_k, top_p, thr_out);
+               finished_in, row_ids, temp, top_k, top_p, thr_out, StepArgs{});
+}
+
+// top-k (optionally followed by the nucleus) and the sampling step in one launch; false if the shape does not
+// qualify (then the caller runs the threshold kernel and the step kernel one after the other)
+bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p, as_status *st)
+{
+    const size_t esz = ctx->dtype == AS_BF16 ? 2 : 4;
+    const bool has_k = top_k > 0 && top_k < ctx->V, has_p = top_p > 0.f && top_p < 1.f;
+    if (ctx->thr_path != 0 || !has_k || top_k > kThreads / 2 || ctx->V > 32768 ||
+        reinterpret_cast<uintptr_t>(a.logits) % 16 != 0 || (a.ld * esz) % 16 != 0)
+        return false;
+    *st = AS_OK;
+    if (a.rows == 0) return true;
+    const dim3 grid((unsigned)a.rows), block(kThreads);
+    if (ctx->dtype == AS_BF16) {
+        if (has_p)
+            launch(ctx, kKernelStep, threshold_resident_kernel<AS_BF16, true, true, true>, grid, block, 0, a.logits, a.ld,
+                   ctx->V, a.finished_in, a.row_ids, a.temp, top_k, top_p, (float *)nullptr, a);
+        else
+            launch(ctx, kKernelStep, threshold_resident_kernel<AS_BF16, true, false, true>, grid, block, 0, a.logits, a.ld,
+                   ctx->V, a.finished_in, a.row_ids, a.temp, top_k, top_p, (float *)nullptr, a);
+    } else {
+        if (has_p)
+            launch(ctx, kKernelStep, threshold_resident_kernel<AS_F32, true, true, true>, grid, block, 0, a.logits, a.ld,
+                   ctx->V, a.finished_in, a.row_ids, a.temp, top_k, top_p, (float *)nullptr, a);
+        else
+            launch(ctx, kKernelStep, threshold_resident_kernel<AS_F32, true, false, true>, grid, block, 0, a.logits, a.ld,
+                   ctx->V, a.finished_in, a.row_ids, a.temp, top_k, top_p, (float *)nullptr, a);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) *st = hip_fail(ctx, e, "fused top-k step launch");
+    return true;
 }
 
 as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
