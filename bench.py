@@ -131,7 +131,9 @@ def main():
                    "storage": cfg["dtype"], "rows": R, "decode_steps": T,
                    "value_with_dispatch_events": code_steps / (t3 - t2)},
         "roofline": {
-            "kernel": "step_kernel (fused sampling step), as launched inside as_decode",
+            "kernel": ("threshold_resident_kernel with the sampling step fused (top-k rows), as launched inside "
+                       "as_decode" if 0 < top_k <= 128 else
+                       "step_kernel (fused sampling step), as launched inside as_decode"),
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
             "avg_launch_us": step_avg_us, "launches": step_n, "untimed_launches": step_drop,

@@ -213,6 +213,17 @@ def test_decode_large_vocab_lockstep():
     _lockstep(cfg, 2, 8, 3)
 
 
+@pytest.mark.parametrize("cfg_id", [1, 2, 3])
+def test_decode_full_size_sampled_steps(cfg_id):
+    """The benchmark's own shapes (all rows, all steps, the launch configurations bench.py times): the whole
+    decode must equal the loop of exported calls, and a sample of steps is checked row by row against the
+    oracle (every row of those steps)."""
+    cfg = dict(synth.CONFIGS[cfg_id])
+    T = cfg["T"]
+    _, _, _, _, _, totals = _lockstep(cfg, cfg["B"], cfg["N"], T, check_steps={0, 1, T // 2, T - 1}, nthreads=16)
+    assert totals["rows"] >= 3 * cfg["B"] * cfg["N"] // 2
+
+
 def test_wide_lattice_first_step_counts_and_monotonicity():
     """One prompt, N = 65536 codes: the first step's row is shared by all codes,
     so per-token counts must be floor/ceil of N*p (up to the fp32 rounding of the
