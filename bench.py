@@ -13,7 +13,8 @@ Prints ONE JSON line: whole-job code-steps/s, plus
                 taken from the dispatch's own HIP events during the timed region
   roofline_cold the same kernel launched alone over >1 GiB of rotating logits
                 buffers, so no row can be served from the 256 MB Infinity Cache
-  roofline_16x_rows  the same kernel, one launch over 16x the rows (1 GiB)
+  roofline_16x_rows  (only with --rows16x) the same kernel, one launch over
+                16x the rows (1 GiB)
   fused_decode  the decode without the logits round trip (as_decode_fused)
   encode        the encode direction over the decoded sequences (as_encode)
   logits_gemm   the MFMA logits kernel: achieved TFLOP/s against the bf16 peak
@@ -40,6 +41,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold (rotating buffers) kernel leg")
+    ap.add_argument("--rows16x", action="store_true",
+                    help="add the leg that runs the sampling kernel once over 16x the rows (its launches carry the "
+                         "same kernel name, so a kernel trace of a run with this flag averages over both sizes)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of a known size (256 MiB each), the yardstick for "
                          "reading rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -254,7 +258,7 @@ def main():
 
     # ---- the same kernel where a launch is long enough to amortise its fixed costs: 16x the rows, one launch
     # over a 1 GiB logits buffer (nothing of it fits the Infinity Cache by the time it is read again)
-    if not args.no_cold and args.config == 1:
+    if args.rows16x and args.config == 1:
         Rl = 16 * R
         ld = (V + 7) // 8 * 8
         ctxl = B.Ctx(Rl, V, tdt)
