@@ -65,6 +65,55 @@ __device__ __forceinline__ void for_row(const T *row, int32_t V, G g)
     }
 }
 
+// The same visit over a row that one pass of 16-byte loads has left in registers: piece u*kThreads + thread of
+// the row sits in w[u], so a thread meets its pieces in the order for_row gives them.
+template <class T, int NP>
+struct ResidentRow {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static constexpr int EPP = 16 / (int)sizeof(T);
+    u32x4 w[NP];
+
+    __device__ __forceinline__ void load(const T *row, int32_t V)
+    {
+        const int32_t npieces = (V + EPP - 1) / EPP;
+#pragma unroll
+        for (int u = 0; u < NP; ++u) {
+            const int32_t piece = u * kThreads + (int32_t)threadIdx.x;
+            w[u] = piece < npieces ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + piece)
+                                   : u32x4{0, 0, 0, 0};
+        }
+    }
+    // between two visits: the compiler must not carry the unpacked values of one over to the next, or the
+    // row is held twice
+    __device__ __forceinline__ void forget()
+    {
+#pragma unroll
+        for (int u = 0; u < NP; ++u) asm volatile("" : "+v"(w[u]));
+    }
+    template <class G>
+    __device__ __forceinline__ void visit(int32_t V, G g) const
+    {
+#pragma unroll
+        for (int u = 0; u < NP; ++u) {
+            const int32_t v0 = (u * kThreads + (int32_t)threadIdx.x) * EPP;
+            if (v0 >= V) break;
+            float x[EPP];
+#pragma unroll
+            for (int e = 0; e < EPP; ++e) {
+                if constexpr (sizeof(T) == 2) {
+                    const uint32_t word = w[u][e >> 1];
+                    x[e] = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
+                } else {
+                    const uint32_t word = w[u][e];
+                    x[e] = __builtin_bit_cast(float, word);
+                }
+            }
+            const int n = V - v0 < EPP ? V - v0 : EPP;
+            g(v0, x, n, std::integral_constant<int, EPP>{});
+        }
+    }
+};
+
 // block-wide sum in a fixed order: lanes by the wave scan, then the waves in index order
 __device__ __forceinline__ double block_sum(double x, double *scratch)
 {
@@ -78,9 +127,12 @@ __device__ __forceinline__ double block_sum(double x, double *scratch)
     return t;
 }
 
-template <class T, bool VEC>
+// MODE 0: element by element; 1: 16-byte pieces, two passes over memory; 4, 8, 16: the row fits in that
+// many pieces per thread and is read once (the arithmetic and its order are the same in all of them).
+template <class T, int MODE>
 __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
 {
+    constexpr bool RES = MODE >= 4;
     __shared__ double scratch[kThreads / 64];
     __shared__ float fscratch[kThreads / 64];
     const int64_t r = blockIdx.x;
@@ -98,33 +150,70 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
     const float thr = a.thr ? a.thr[r] : -__builtin_inff();
     const float k = a.k;
 
-    float m = -__builtin_inff();
-    for_row<T, VEC>(row, a.V, [&](int32_t, const float *x, int n, auto cap) {
+    ResidentRow<T, RES ? MODE : 1> res;
+    if constexpr (RES) res.load(row, a.V);
+    auto each_run = [&](auto g) __attribute__((always_inline)) {
+        if constexpr (RES) res.visit(a.V, g);
+        else for_row<T, MODE == 1>(row, a.V, g);
+    };
+
+    // a run as the sums see it: what is cut off by the threshold or lies past the row's end counts as -inf
+    // (weight exactly 0); whole runs of an untruncated row, nearly all of them, pass through untouched
+    const bool cut = a.thr != nullptr;
+    auto kept = [&](const float *x, int n, auto cap, float *y) __attribute__((always_inline)) {
+        constexpr int E = decltype(cap)::value;
+        if (!cut && n == E) {
 #pragma unroll
-        for (int e = 0; e < decltype(cap)::value; ++e)
-            if (e < n && x[e] >= thr) m = fmaxf(m, x[e]);
+            for (int e = 0; e < E; ++e) y[e] = x[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) y[e] = (e < n && x[e] >= thr) ? x[e] : -__builtin_inff();
+        }
+    };
+
+    float m = -__builtin_inff();
+    each_run([&](int32_t, const float *x, int n, auto cap) __attribute__((always_inline)) {
+        constexpr int E = decltype(cap)::value;
+        float y[E];
+        kept(x, n, cap, y);
+#pragma unroll
+        for (int e = 0; e < E; ++e) m = fmaxf(m, y[e]);
     });
+    if constexpr (RES) res.forget();
     m = wave_max(m);
     if ((threadIdx.x & 63) == 0) fscratch[threadIdx.x >> 6] = m;
     __syncthreads();
     m = fscratch[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fscratch[w]);
-    const float ref = fmaxf(ceilf(m * k), -100000.f);
+    const float nref = -fmaxf(ceilf(m * k), -100000.f);
 
-    // per run: fp32 sums of at most 8 weights, then one fp64 add per total
+    // per run: fp32 sum of its (at most 8) weights in order, then one fp64 add per total; only the one run
+    // that holds the token looks at single weights
     double all = 0.0, before = 0.0, at = 0.0;
-    for_row<T, VEC>(row, a.V, [&](int32_t v0, const float *x, int n, auto cap) {
-        float s_all = 0.f, s_before = 0.f;
+    each_run([&](int32_t v0, const float *x, int n, auto cap) __attribute__((always_inline)) {
+        constexpr int E = decltype(cap)::value;
+        float y[E], w[E];
+        kept(x, n, cap, y);
+        float s_all = 0.f;
 #pragma unroll
-        for (int e = 0; e < decltype(cap)::value; ++e) {
-            const float w = (e < n && x[e] >= thr) ? __builtin_amdgcn_exp2f(fmaf(x[e], k, -ref)) : 0.f;
-            s_all += w;
-            s_before += v0 + e < tok ? w : 0.f;
-            if (v0 + e == tok) at = (double)w;
+        for (int e = 0; e < E; ++e) {
+            w[e] = __builtin_amdgcn_exp2f(fmaf(y[e], k, nref));
+            s_all += w[e];
         }
-        all += (double)s_all;
-        before += (double)s_before;
+        const double d = (double)s_all;
+        all += d;
+        if (v0 + E <= tok) {
+            before += d;
+        } else if (v0 <= tok) {
+            float s_before = 0.f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                s_before += v0 + e < tok ? w[e] : 0.f;
+                if (v0 + e == tok) at = (double)w[e];
+            }
+            before += (double)s_before;
+        }
     });
     all = block_sum(all, scratch);
     before = block_sum(before, scratch);
@@ -160,13 +249,20 @@ as_status launch_interval(as_ctx *ctx, const IntervalArgs &a)
     const size_t esz = a.dtype == AS_BF16 ? 2 : 4;
     const bool vec = reinterpret_cast<uintptr_t>(a.logits) % 16 == 0 && (a.ld * esz) % 16 == 0;
     const dim3 grid((unsigned)a.rows), block(kThreads);
-    if (a.dtype == AS_BF16) {
-        if (vec) launch(ctx, kKernelInterval, interval_kernel<uint16_t, true>, grid, block, 0, a);
-        else launch(ctx, kKernelInterval, interval_kernel<uint16_t, false>, grid, block, 0, a);
-    } else {
-        if (vec) launch(ctx, kKernelInterval, interval_kernel<float, true>, grid, block, 0, a);
-        else launch(ctx, kKernelInterval, interval_kernel<float, false>, grid, block, 0, a);
+    // pieces per thread when the whole row is to stay in registers (at most 16: 64 registers)
+    const int64_t per_thread = ((int64_t)a.V * (int64_t)esz + 16 * kThreads - 1) / (16 * kThreads);
+    const int mode = !vec ? 0 : ctx->interval_path == 1 || per_thread > 16 ? 1 : per_thread <= 4 ? 4
+                                                                             : per_thread <= 8 ? 8 : 16;
+#define AS_INTERVAL_LAUNCH(T)                                                                          \
+    switch (mode) {                                                                                    \
+    case 0: launch(ctx, kKernelInterval, interval_kernel<T, 0>, grid, block, 0, a); break;             \
+    case 1: launch(ctx, kKernelInterval, interval_kernel<T, 1>, grid, block, 0, a); break;             \
+    case 4: launch(ctx, kKernelInterval, interval_kernel<T, 4>, grid, block, 0, a); break;             \
+    case 8: launch(ctx, kKernelInterval, interval_kernel<T, 8>, grid, block, 0, a); break;             \
+    default: launch(ctx, kKernelInterval, interval_kernel<T, 16>, grid, block, 0, a); break;           \
     }
+    if (a.dtype == AS_BF16) { AS_INTERVAL_LAUNCH(uint16_t) } else { AS_INTERVAL_LAUNCH(float) }
+#undef AS_INTERVAL_LAUNCH
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }
