@@ -33,6 +33,14 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
 
+def spread(samples_ms):
+    """median / p10 / p90 of single launch durations, in microseconds"""
+    if len(samples_ms) == 0:
+        return None
+    q = np.percentile(np.asarray(samples_ms, dtype=np.float64) * 1e3, [50, 10, 90])
+    return {"median_us": float(q[0]), "p10_us": float(q[1]), "p90_us": float(q[2]), "launches": int(len(samples_ms))}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +107,8 @@ def main():
         decode()
     torch.cuda.synchronize()
     t3 = time.perf_counter()
+    step_samples = ctx.profile_samples(0)
+    gemm_samples = ctx.profile_samples(1)
     step_ms, step_n, step_drop = ctx.profile_read(0)
     gemm_ms, gemm_n, _ = ctx.profile_read(1)
     thr_ms, thr_n, _ = ctx.profile_read(2)
@@ -151,6 +161,14 @@ def main():
     }
     if out["logits_gemm"]["achieved"]:
         out["logits_gemm"]["frac"] = out["logits_gemm"]["achieved"] / MFMA_BF16_PEAK_TFLOPS
+    out["roofline"]["spread"] = spread(step_samples)
+    out["logits_gemm"]["spread"] = spread(gemm_samples)
+    if len(step_samples) == T * args.steps and T >= 4:
+        # by position in the decode: the first step (every row of a prompt starts from the same token, so the
+        # logits rows repeat N times) against the second half (rows have gone their own ways; some have finished)
+        by_step = np.asarray(step_samples).reshape(args.steps, T)
+        out["roofline"]["first_step"] = spread(by_step[:, 0])
+        out["roofline"]["late_steps"] = spread(by_step[:, T // 2:].ravel())
     if thr_n:
         out["threshold_kernel"] = {"avg_launch_us": thr_ms / thr_n * 1e3, "launches": thr_n}
 
@@ -245,11 +263,13 @@ def main():
         for _ in range(reps):
             for i in range(nbuf):
                 B.as_step(ctx, bufs[i], codes, temp, top_k, top_p, tok, cout)
+        cold_samples = ctx.profile_samples(0)
         ms, n, _ = ctx.profile_read(0)
         ctx.profile(False)
         us = ms / n * 1e3
         ach = R * bytes_per_row / (us * 1e-6) / 1e9
         out["roofline_cold"] = {
+            "spread": spread(cold_samples),
             "kernel": "step_kernel alone, rotating over %d logits buffers (%.2f GiB)" % (
                 nbuf, nbuf * R * ld * esz / 2 ** 30),
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
@@ -309,7 +329,19 @@ def main():
             if time.perf_counter() - c0 > 1.5:
                 break
         c1 = time.perf_counter()
+        # the same on one thread, over fewer rows
+        one_rows = min(R, 64)
+        o0 = time.perf_counter()
+        one_reps = 0
+        while True:
+            oracle.step(stored[:one_rows], codes[:one_rows], temp=temp, top_k=top_k, top_p=top_p, V=V, nthreads=1)
+            one_reps += 1
+            if time.perf_counter() - o0 > 0.5:
+                break
+        o1 = time.perf_counter()
         out["cpu_baseline"] = {
+            "one_thread": {"value": one_rows * one_reps / (o1 - o0), "unit": "code-steps/s",
+                           "sample": f"the first {one_rows} rows, {one_reps} repetitions, {o1 - o0:.2f} s"},
             "value": sample_rows * reps / (c1 - c0), "unit": "code-steps/s", "cores": nthreads, "kind": "oracle",
             "sample": f"oracle step (fp64) over the {sample_rows} rows of the first decode step's logits, "
                       f"{reps} repetitions, {nthreads} OpenMP threads, {c1 - c0:.2f} s wall; sampling step "

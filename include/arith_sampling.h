@@ -91,6 +91,13 @@ const char *as_last_error(const as_ctx *ctx);
 as_status as_ctx_profile(as_ctx *ctx, int enable);
 as_status as_ctx_profile_read(as_ctx *ctx, int kernel, double *total_ms,
                               int64_t *launches, int64_t *untimed);
+/* The single durations behind that sum, for medians and percentiles: copies the
+ * milliseconds of the first min(capacity, timed launches) launches of `kernel`
+ * since the last read, in launch order, to the HOST array ms_out, and stores the
+ * number of timed launches in *count (may be NULL).  Synchronises the stream;
+ * resets nothing, so call it before as_ctx_profile_read. */
+as_status as_ctx_profile_samples(as_ctx *ctx, int kernel, float *ms_out,
+                                 int64_t capacity, int64_t *count);
 
 /* ------------------------------------------------------------ single step */
 

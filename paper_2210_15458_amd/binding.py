@@ -54,6 +54,8 @@ def lib():
     L.as_step_fused.argtypes = [vp, vp, vp, i64, vp, i64, vp, f32, vp, vp, vp, i32, vp]
     L.as_ctx_profile.argtypes = [vp, C.c_int]
     L.as_ctx_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(i64)]
+    L.as_ctx_profile_samples.argtypes = [vp, C.c_int, C.POINTER(C.c_float), i64, C.POINTER(i64)]
+    L.as_ctx_profile_samples.restype = C.c_int
     L.as_ctx_profile.restype = C.c_int
     L.as_ctx_profile_read.restype = C.c_int
     for name in ("as_ctx_create", "as_ctx_destroy", "as_step", "as_step_ex", "as_lattice",
@@ -116,6 +118,15 @@ class Ctx:
         ms, n, dropped = C.c_double(), C.c_int64(), C.c_int64()
         self._check(lib().as_ctx_profile_read(self._h, int(kernel), C.byref(ms), C.byref(n), C.byref(dropped)))
         return ms.value, n.value, dropped.value
+
+    def profile_samples(self, kernel, capacity=16384):
+        """Milliseconds of each timed launch since the last read, in launch order (call before profile_read)."""
+        import numpy as np
+        buf = np.empty(capacity, dtype=np.float32)
+        n = C.c_int64()
+        self._check(lib().as_ctx_profile_samples(self._h, int(kernel), buf.ctypes.data_as(C.POINTER(C.c_float)),
+                                                 capacity, C.byref(n)))
+        return buf[:min(n.value, capacity)].copy()
 
     def close(self):
         if self._h:

@@ -174,6 +174,20 @@ as_status as_ctx_profile_read(as_ctx *ctx, int kernel, double *total_ms, int64_t
     return AS_OK;
 }
 
+as_status as_ctx_profile_samples(as_ctx *ctx, int kernel, float *ms_out, int64_t capacity, int64_t *count)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (kernel < 0 || kernel >= kKernelCount) return fail(ctx, AS_ERR_INVALID_ARG, "unknown kernel id");
+    if (capacity < 0 || (capacity > 0 && !ms_out)) return fail(ctx, AS_ERR_INVALID_ARG, "ms_out is NULL");
+    AS_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    Profile &p = ctx->prof;
+    const int64_t n = (int64_t)p.used[kernel] < capacity ? (int64_t)p.used[kernel] : capacity;
+    for (int64_t i = 0; i < n; ++i)
+        AS_HIP_TRY(ctx, hipEventElapsedTime(&ms_out[i], p.slots[kernel][i].start, p.slots[kernel][i].stop));
+    if (count) *count = (int64_t)p.used[kernel];
+    return AS_OK;
+}
+
 as_status as_step_ex(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, const float *codes, float temp,
                      int32_t top_k, float top_p, int32_t *tokens_out, float *codes_out,
                      const uint8_t *finished_in, int32_t eos_id, uint8_t *finished_out, float *prob_out,
