@@ -116,7 +116,8 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
                                                                  const uint16_t *__restrict__ Ut,
                                                                  const int32_t *__restrict__ prev, int64_t R,
                                                                  int32_t V, int32_t d, float alpha,
-                                                                 OutT *__restrict__ C, int64_t ldc, int vec_store)
+                                                                 OutT *__restrict__ C, int64_t ldc, int vec_store,
+                                                                 int gm)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kPersistLds];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -125,7 +126,9 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
     // Work-groups are handed to the 8 XCDs round-robin, so block b runs on XCD b & 7 and is worker b >> 3 of
     // the W workers there.  XCD x owns column tiles x, x+8, ...  A worker keeps one row tile as long as it can
     // (its gathered A rows stay the same from tile to tile) and the workers of an XCD sit on the same few
-    // column tiles at the same time, so a Ut tile is fetched into that XCD's L2 once.
+    // column tiles at the same time, so a Ut tile is fetched into that XCD's L2 once.  With more row tiles
+    // than workers, the W workers of an XCD stand gm x W/gm over row and column tiles: what they have open
+    // at one time, gm A tiles and W/gm Ut tiles, has to fit that XCD's L2 or every tile refetches both.
     const int64_t m_blocks = (R + PM - 1) / PM;
     const int64_t n_blocks = ((int64_t)V + PN - 1) / PN;
     const int W = (int)(gridDim.x >> 3);
@@ -134,9 +137,12 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
     const int64_t cg = m_blocks < W ? W / m_blocks : 0;
     auto item = [&](int64_t j, int64_t &bm, int64_t &bn) __attribute__((always_inline)) -> bool {
         if (nbx <= 0) return false;
-        if (m_blocks >= W) {
-            bm = q + W * (j / nbx);
-            bn = xcd + 8 * (j % nbx);
+        if (m_blocks >= W || (m_blocks >= gm && m_blocks % gm == 0)) {
+            const int gn = W / gm, qm = q % gm, qn = q / gm;        // host: gm divides W
+            if (nbx <= qn) return false;
+            const int64_t mine = (nbx - qn + gn - 1) / gn;         // column tiles of this XCD that are this worker's
+            bm = qm + gm * (j / mine);
+            bn = xcd + 8 * (qn + gn * (j % mine));
             return bm < m_blocks;
         }
         if (q >= cg * m_blocks) return false;
@@ -707,6 +713,16 @@ as_status launch_transpose(const void *U, void *Ut, int32_t d, int32_t V, as_dty
     return AS_OK;
 }
 
+// Workers of an XCD along the row tiles when there are more row tiles than workers (a divisor of their number)
+static int persistent_gm(const as_ctx *ctx)
+{
+    const int W = ctx->num_cus / 8;
+    if (ctx->gemm_gm > 0 && W % ctx->gemm_gm == 0) return ctx->gemm_gm;
+    // 8 x W/8: with 256 KB per operand tile (d = 512) that is 2 MB of A and 1 MB of Ut open in a 4 MB L2;
+    // measured at 65536 x 32128 x 512: 768 TFLOP/s with all workers along the rows, 992 with 8, 938 with 4
+    return W % 8 == 0 ? 8 : W;
+}
+
 as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *prev, int64_t rows,
                                void *logits_out, int64_t ld)
 {
@@ -725,10 +741,10 @@ as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *pr
             const dim3 grid((unsigned)(8 * (ctx->num_cus / 8))), block(512);
             if (ctx->dtype == AS_BF16)
                 launch(ctx, kKernelLogits, bigram_gemm_persistent<uint16_t>, grid, block, 0, Ep, Up, prev, rows,
-                       m->V, m->d, alpha, (uint16_t *)logits_out, ld, vec_store);
+                       m->V, m->d, alpha, (uint16_t *)logits_out, ld, vec_store, persistent_gm(ctx));
             else
                 launch(ctx, kKernelLogits, bigram_gemm_persistent<float>, grid, block, 0, Ep, Up, prev, rows, m->V,
-                       m->d, alpha, (float *)logits_out, ld, vec_store);
+                       m->d, alpha, (float *)logits_out, ld, vec_store, persistent_gm(ctx));
         } else {
             // grid: 8 XCD lanes x ceil(column tiles / 8) x row tiles (see the kernel's tile mapping)
             const int64_t m_blocks = (rows + BM - 1) / BM, n_blocks = ((int64_t)m->V + BN - 1) / BN;
@@ -773,7 +789,8 @@ as_status launch_bigram_partials(as_ctx *ctx, const as_model *m, const int32_t *
     const float alpha = (float)((double)m->scale / sqrt((double)m->d) * 1.44269504088896340736 / (double)temp);
     const dim3 grid((unsigned)(8 * (ctx->num_cus / 8))), block(512);
     launch(ctx, kKernelLogits, bigram_gemm_persistent<float, true>, grid, block, 0, (const uint16_t *)m->E,
-           (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha, reinterpret_cast<float *>(part), ldp, 0);
+           (const uint16_t *)m->Ut, prev, rows, m->V, m->d, alpha, reinterpret_cast<float *>(part), ldp, 0,
+           persistent_gm(ctx));
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }

@@ -600,7 +600,6 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
                 }
             }
             __syncthreads();
-            const float pickf = (float)sh.pick;
             before = (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
             __syncthreads();
             // the logits of that bin go to the candidate table
@@ -609,33 +608,68 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
             float nr2 = nr;
             asm volatile("" : "+v"(nr2));
             forget_row();
-            auto maybe_candidate = [&](uint32_t bits) __attribute__((always_inline)) {
+            // The coarse bin is monotone in the logit, so the logits of one bin are one interval of values:
+            // its ends by bisection over the keys between -inf and +inf (the same few steps in every thread),
+            // and the pass over the row is two compares per logit.
+            const int pick_bin = (int)sh.pick;
+            auto first_key_with_bin_at_most = [&](int b) __attribute__((always_inline)) {
+                uint32_t lo = kHalf ? 0x007fu : 0x007fffffu, hi = kHalf ? 0xff80u : 0xff800000u;
+                while (lo < hi) {                      // bin(hi) = 0 <= b always holds
+                    const uint32_t mid = lo + ((hi - lo) >> 1);
+                    if (coarse_bin(fmaf(K::from_key(mid), k, nr2)) <= b) hi = mid;
+                    else lo = mid + 1;
+                }
+                return lo;
+            };
+            const float xlo = K::from_key(first_key_with_bin_at_most(pick_bin));
+            const float xhi = pick_bin > 0 ? K::from_key(first_key_with_bin_at_most(pick_bin - 1)) : __builtin_inff();
+            auto in_bin = [&](uint32_t bits) __attribute__((always_inline)) {
                 const float x = __builtin_bit_cast(float, bits);
-                const float y = fmaf(x, k, nr2);
-                const float t = fminf(fmaxf(-y * 64.f, 0.f), (float)(kCoarseBins - 1));   // as in coarse_bin
-                if (t >= pickf && t < pickf + 1.f) {
-                    const unsigned long long q = mass_q(x, k, nr2);
-                    if (q) {
-                        const uint32_t i = atomicAdd(&sh.ncand, 1u);
-                        if (i < (uint32_t)kCandCap) {
-                            sh.ckey[i] = kHalf ? K::key((T)(bits >> 16)) : K::key(__builtin_bit_cast(T, (typename std::conditional<kHalf, uint16_t, uint32_t>::type)bits));
-                            sh.cq[i] = (uint32_t)q;
-                        }
+                return (x >= xlo) & (x < xhi);
+            };
+            auto candidate = [&](uint32_t bits) __attribute__((always_inline)) {
+                const float x = __builtin_bit_cast(float, bits);
+                const unsigned long long q = mass_q(x, k, nr2);
+                if (q) {
+                    const uint32_t i = atomicAdd(&sh.ncand, 1u);
+                    if (i < (uint32_t)kCandCap) {
+                        sh.ckey[i] = kHalf ? K::key((T)(bits >> 16)) : K::key(__builtin_bit_cast(T, (typename std::conditional<kHalf, uint16_t, uint32_t>::type)bits));
+                        sh.cq[i] = (uint32_t)q;
                     }
                 }
             };
+            // branch-free over the registers: which of this thread's pieces hold a logit of the bin
+            uint32_t hot = 0;
 #pragma unroll
-            for (int p = 0; p < NP; ++p)
+            for (int p = 0; p < NP; ++p) {
+                bool any = false;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t w = pc[p][i];
+                    if constexpr (kHalf) any |= in_bin(w << 16) | in_bin(w & 0xffff0000u);
+                    else any |= in_bin(w);
+                }
+                hot |= any ? 1u << p : 0u;
+            }
+            // those few pieces once more from memory (a loop over set bits cannot index registers), one body
+            // of code for all of them
+            while (hot) {
+                const int p = __builtin_ctz(hot);
+                hot &= hot - 1;
+                const int32_t piece = p * kThreads + tid;
+                const u32x4 again = reinterpret_cast<const u32x4 *>(row)[piece];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = again[i];
                     if constexpr (kHalf) {
-                        maybe_candidate(w << 16);
-                        maybe_candidate(w & 0xffff0000u);
+                        const int32_t v = piece * EPP + 2 * i;
+                        if (v < V && in_bin(w << 16)) candidate(w << 16);
+                        if (v + 1 < V && in_bin(w & 0xffff0000u)) candidate(w & 0xffff0000u);
                     } else {
-                        maybe_candidate(w);
+                        if (piece * EPP + i < V && in_bin(w)) candidate(w);
                     }
                 }
+            }
             __syncthreads();
             ncand = sh.ncand;
             if (ncand > (uint32_t)kCandCap) fall = true;

@@ -58,8 +58,32 @@ _GEMM_CASES = [
     (5000, 128, "bf16", "bf16", 300, 0, 0), (1003, 128, "bf16", "bf16", 300, 5, 0), (1003, 128, "bf16", "f32", 260, 1, 0),
     # ... more row tiles than workers per XCD: every worker changes its row tile between tiles
     (2500, 128, "bf16", "bf16", 8200, 0, 0),
+    # ... sixteen row tiles: the workers of an XCD stand 8 x 4 over row and column tiles, two row tiles each
+    (9000, 128, "bf16", "bf16", 4096, 0, 0),
     # the tile kernel on the headline shape
     (32128, 512, "bf16", "bf16", 130, 0, 1), (32128, 512, "bf16", "f32", 40, 0, 1)]
+
+
+@pytest.mark.parametrize("gm", [32, 4, 1])
+def test_bigram_logits_worker_placement(gm, monkeypatch):
+    """How the persistent kernel's workers are spread over the tiles changes which block computes a tile, not
+    what the tile holds: every placement gives the default one's logits bit for bit."""
+    import torch
+    from paper_2210_15458_amd import binding as B
+    V, d, R = 2500, 128, 8200 + 256 * 3
+    _, _, model = _upload_model(V, d, "bf16")
+    prev = torch.from_numpy(np.random.default_rng(2).integers(0, V, R).astype(np.int32)).cuda()
+    outs = []
+    for knob in (None, gm):
+        if knob is not None:
+            monkeypatch.setenv("AS_GEMM_GM", str(knob))
+        ctx = B.Ctx(R, V, torch.bfloat16)
+        out = torch.full((R, (V + 7) // 8 * 8), 7.0, dtype=torch.bfloat16, device="cuda")
+        B.as_bigram_logits(ctx, model, prev, out)
+        torch.cuda.synchronize()
+        outs.append(out.view(torch.int16).cpu())
+        ctx.close()
+    assert torch.equal(outs[0], outs[1])
 
 
 @pytest.mark.parametrize("V,d,wdtype,ldtype,R,ldpad,knob", _GEMM_CASES)
