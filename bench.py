@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations")
+    ap.add_argument("--top-k", type=int, default=None, help="override the configuration's top_k (0 = off)")
+    ap.add_argument("--top-p", type=float, default=None, help="override the configuration's top_p (1 = off)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold (rotating buffers) kernel leg")
     ap.add_argument("--rows16x", action="store_true",
@@ -68,6 +70,10 @@ def main():
     cfg = synth.CONFIGS[args.config]
     V, d, Bn, N, T = cfg["V"], cfg["d"], cfg["B"], cfg["N"], cfg["T"]
     temp, top_k, top_p, eos = cfg["temp"], cfg["top_k"], cfg["top_p"], cfg["eos_id"]
+    if args.top_k is not None:
+        top_k = args.top_k
+    if args.top_p is not None:
+        top_p = args.top_p
     R = Bn * N
     tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
     esz = 2 if cfg["dtype"] == "bf16" else 4

@@ -297,15 +297,25 @@ __device__ __forceinline__ uint32_t wave_reduce_umin(uint32_t x)
     return x;
 }
 
-// Coarse bin of a logit whose exponent argument (base 2, relative to the row's reference) is y <= 0.
+// Coarse bin of a logit from its exponent argument y (base 2, relative to the row's reference): -64*y rounded
+// to the nearest integer (adding 2^23 leaves it in the low mantissa bits) and clamped to the table; monotone
+// in y.  The second form is for y <= 0, which is every logit of the row itself, and agrees with the first there.
 __device__ __forceinline__ int coarse_bin(float y)
 {
-    const float b = fminf(fmaxf(-y * 64.f, 0.f), (float)(kCoarseBins - 1));
-    return (int)b;
+    float t = fmaf(y, -64.f, 8388608.f);
+    t = fminf(fmaxf(t, 8388608.f), 8388608.f + (float)(kCoarseBins - 1));
+    return (int)(__builtin_bit_cast(uint32_t, t) - 0x4B000000u);
+}
+__device__ __forceinline__ int coarse_bin_nonpositive(float y)
+{
+    const float t = fminf(fmaf(y, -64.f, 8388608.f), 8388608.f + (float)(kCoarseBins - 1));
+    return (int)(__builtin_bit_cast(uint32_t, t) - 0x4B000000u);
 }
 
-// STEP (with HAS_K): go on and finish the sampling step for the row from the candidate table -- after top-k
-// every kept logit is in it, so the row is not read a second time.  sa then carries the step's arguments.
+// STEP: go on and finish the sampling step for the row, which is then not read a second time.  With HAS_K from
+// the candidate table (after top-k every kept logit is in it); with the nucleus alone, where most of the row
+// can be kept, from the registers (bf16 rows: their 4096 sums of 8 logits take the histogram's place in LDS).
+// sa then carries the step's arguments.
 template <int DT, bool HAS_K, bool HAS_P, bool STEP = false>
 __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void *logits, int64_t ld, int32_t V,
                                                                       const uint8_t *finished_in,
@@ -313,7 +323,8 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
                                                                       int32_t top_k, float top_p, float *thr_out,
                                                                       StepArgs sa)
 {
-    static_assert(!STEP || HAS_K, "the fused step works on the top-k candidate table");
+    static_assert(!STEP || HAS_K || (HAS_P && DT == AS_BF16),
+                  "the fused step works on the top-k candidate table, or for a bf16 row on its registers");
     using K = Key<DT>;
     using T = typename K::T;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -505,6 +516,7 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
     }
 
     // ---------------- nucleus over the survivors
+    float nr_row = 0.f;                  // minus the row's integer reference, as the nucleus pass took it
     if (HAS_P && !fall) {
         const float k = 1.44269504088896340736f / temp;
         double need;
@@ -556,6 +568,7 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
 #pragma unroll
             for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
             const float nr = -fmaxf(ceilf(m * k), -100000.f);
+            nr_row = nr;
             __syncthreads();
             // mass per coarse bin, in the fixed point of the radix path
             forget_row();
@@ -563,7 +576,7 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
                 const float y = fmaf(x, k, nr);
                 const float e = __builtin_amdgcn_exp2f(y);
                 const uint32_t q = (uint32_t)(e * 2147483648.f + 0.5f);
-                if (q) atomicAdd(&sh.hist[coarse_bin(y)], (unsigned long long)q);
+                if (q) atomicAdd(&sh.hist[coarse_bin_nonpositive(y)], (unsigned long long)q);
             };
 #pragma unroll
             for (int p = 0; p < NP; ++p)
@@ -706,6 +719,103 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
             generic_step_row<T>(sa, r, K::from_key(thr_key), sc.gen);
             return;
         }
+        if constexpr (!HAS_K) {
+            // ---- the sampling step from the registers (Sec. 4.1 loop body).  Weights exp2(x*k - ref) of the
+            // kept logits against the reference of the nucleus pass; per piece of 8 an fp32 sum in vocabulary
+            // order; fp64 from there on.  The bucket is the last piece, then the last logit in it, that has
+            // weight and whose mass before it does not exceed c*S: with c*S inside the row that is the one
+            // it falls into, and past the end by rounding it is the last kept token.
+            const float k = sa.k;
+            const float thr = K::from_key(thr_key);
+            float nr3 = nr_row;
+            asm volatile("" : "+v"(nr3));
+            forget_row();
+            float *psum = reinterpret_cast<float *>(sh.hist);            // NP * kThreads = 4096 entries
+            double *dred = reinterpret_cast<double *>(sh.ckey);
+            uint32_t *ured = sh.mcount;
+            auto weight = [&](uint32_t bits) __attribute__((always_inline)) {
+                const float x = __builtin_bit_cast(float, bits);
+                return x >= thr ? fast_exp2(fmaf(x, k, nr3)) : 0.f;
+            };
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = pc[p][i];
+                    sum += weight(w << 16);
+                    sum += weight(w & 0xffff0000u);
+                }
+                psum[p * kThreads + tid] = sum;
+            }
+            __syncthreads();
+            float ent[NP];
+            double local = 0.0;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                ent[i] = psum[tid * NP + i];
+                local += (double)ent[i];
+            }
+            const double incl = wave_scan_add(local);
+            if ((tid & 63) == 63) dred[tid >> 6] = incl;
+            __syncthreads();
+            double base = 0.0, S = 0.0;
+#pragma unroll
+            for (int w = 0; w < kThreads / 64; ++w) {
+                const double t = dred[w];
+                if (w < (tid >> 6)) base += t;
+                S += t;
+            }
+            const double tau = (double)sa.codes[r] * S;
+            uint32_t best = 0;                                           // piece index + 1
+            double best_before = 0.0, acc = base + incl - local;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                if (ent[i] > 0.f && acc <= tau) {
+                    best = (uint32_t)(tid * NP + i) + 1u;
+                    best_before = acc;
+                }
+                acc += (double)ent[i];
+            }
+            const uint32_t wbest = wave_reduce_umax(best);
+            if ((tid & 63) == 0) ured[tid >> 6] = wbest;
+            __syncthreads();
+            uint32_t gbest = ured[0];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) gbest = gbest > ured[w] ? gbest : ured[w];
+            if (best == gbest && gbest != 0u) dred[4] = best_before;
+            __syncthreads();
+            if (tid == 0) {
+                int32_t piece = gbest ? (int32_t)gbest - 1 : 0;
+                if (piece > npieces - 1) piece = npieces - 1;
+                const u32x4 again = reinterpret_cast<const u32x4 *>(row)[piece];
+                double before = gbest ? dred[4] : 0.0, lo = before;
+                float ev = 0.f;
+                int32_t token = piece * EPP;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = again[i];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int32_t v = piece * EPP + 2 * i + h;
+                        const float e = v < V ? weight(h ? (w & 0xffff0000u) : (w << 16)) : 0.f;
+                        if (e > 0.f && before <= tau) {
+                            token = v;
+                            lo = before;
+                            ev = e;
+                        }
+                        before += (double)e;
+                    }
+                }
+                RowOut o;
+                o.token = token;
+                o.c_next = rescale_code(tau, lo, (double)ev);
+                o.prob = (float)((double)ev / S);
+                o.f_lo = (float)(lo / S);
+                write_row(sa, r, o);
+            }
+            return;
+        }
         // ---- the sampling step on the kept candidates (Sec. 4.1 loop body): weights against an integer
         // reference, cumulative sums in vocabulary order, first bucket above the code, rescale
         const float k = sa.k;
@@ -788,19 +898,23 @@ void launch_resident(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, 
                finished_in, row_ids, temp, top_k, top_p, thr_out, StepArgs{});
 }
 
-// top-k (optionally followed by the nucleus) and the sampling step in one launch; false if the shape does not
-// qualify (then the caller runs the threshold kernel and the step kernel one after the other)
+// top-k (optionally followed by the nucleus), or the nucleus alone on bf16 rows, and the sampling step in one
+// launch; false if the shape does not qualify (then the caller runs the threshold kernel and the step kernel one after the other)
 bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p, as_status *st)
 {
     const size_t esz = ctx->dtype == AS_BF16 ? 2 : 4;
     const bool has_k = top_k > 0 && top_k < ctx->V, has_p = top_p > 0.f && top_p < 1.f;
-    if (ctx->thr_path != 0 || !has_k || top_k > kThreads / 2 || ctx->V > 32768 ||
+    const bool nucleus_only = !has_k && has_p && ctx->dtype == AS_BF16;
+    if (ctx->thr_path != 0 || !(has_k || nucleus_only) || top_k > kThreads / 2 || ctx->V > 32768 ||
         reinterpret_cast<uintptr_t>(a.logits) % 16 != 0 || (a.ld * esz) % 16 != 0)
         return false;
     *st = AS_OK;
     if (a.rows == 0) return true;
     const dim3 grid((unsigned)a.rows), block(kThreads);
-    if (ctx->dtype == AS_BF16) {
+    if (nucleus_only) {
+        launch(ctx, kKernelStep, threshold_resident_kernel<AS_BF16, false, true, true>, grid, block, 0, a.logits, a.ld,
+               ctx->V, a.finished_in, a.row_ids, a.temp, top_k, top_p, (float *)nullptr, a);
+    } else if (ctx->dtype == AS_BF16) {
         if (has_p)
             launch(ctx, kKernelStep, threshold_resident_kernel<AS_BF16, true, true, true>, grid, block, 0, a.logits, a.ld,
                    ctx->V, a.finished_in, a.row_ids, a.temp, top_k, top_p, (float *)nullptr, a);
