@@ -237,12 +237,18 @@ def test_decode_large_vocab_lockstep():
     _lockstep(cfg, 2, 8, 3)
 
 
-@pytest.mark.parametrize("cfg_id", [1, 2, 3])
-def test_decode_full_size_sampled_steps(cfg_id):
+@pytest.mark.parametrize("cfg_id,trunc", [(1, "as given"), (2, "as given"), (2, "top-k only"), (2, "nucleus only"),
+                                          (3, "as given")])
+def test_decode_full_size_sampled_steps(cfg_id, trunc):
     """The benchmark's own shapes (all rows, all steps, the launch configurations bench.py times): the whole
     decode must equal the loop of exported calls, and a sample of steps is checked row by row against the
-    oracle (every row of those steps)."""
+    oracle (every row of those steps).  The truncated configuration also in the two separate runs the
+    benchmark describes (top-k alone, nucleus alone)."""
     cfg = dict(synth.CONFIGS[cfg_id])
+    if trunc == "top-k only":
+        cfg["top_p"] = 1.0
+    elif trunc == "nucleus only":
+        cfg["top_k"] = 0
     T = cfg["T"]
     _, _, _, _, _, totals = _lockstep(cfg, cfg["B"], cfg["N"], T, check_steps={0, 1, T // 2, T - 1}, nthreads=16)
     assert totals["rows"] >= 3 * cfg["B"] * cfg["N"] // 2
