@@ -30,19 +30,21 @@ def _interval_step(stored, tokens, V, temp=1.0, top_k=0, top_p=1.0, finished=Non
     return lo.cpu().numpy(), w.cpu().numpy(), None if fin_out is None else fin_out.cpu().numpy()
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("V,ld", [(32128, None), (1001, None), (1001, 1008), (5, None), (256000, None),
-                                  (12000, None), (16384, None), (16392, None)])
-@pytest.mark.parametrize("temp,top_k,top_p", [(1.0, 0, 1.0), (0.7, 0, 1.0), (1.0, 40, 1.0), (1.0, 0, 0.9)])
+_MODS = [(1.0, 0, 1.0), (0.7, 0, 1.0), (1.0, 40, 1.0), (1.0, 0, 0.9)]
+# every form of the kernel: element by element (odd strides), two passes over memory (rows too long for the
+# registers), and the row resident in 4, 8 or 16 pieces per thread, with 16384 and 16392 on either side of a
+# boundary between forms.  All logit modifiers on the general shapes, the untruncated ones on the
+# resident-form shapes, one plain case on the large vocabulary.
+_INTERVAL_CASES = (
+    [(dt, V, ld, *m) for dt in ("bf16", "f32") for (V, ld) in [(32128, None), (1001, None), (1001, 1008), (5, None)]
+     for m in _MODS]
+    + [(dt, V, None, *m) for dt in ("bf16", "f32") for V in (12000, 16384, 16392) for m in _MODS[:2]]
+    + [("bf16", 256000, None, 1.0, 0, 1.0)])
+
+
+@pytest.mark.parametrize("dtype,V,ld,temp,top_k,top_p", _INTERVAL_CASES)
 def test_interval_step_matches_oracle(dtype, V, ld, temp, top_k, top_p):
-    # the shapes span every form of the kernel: element by element (odd strides), two passes over memory
-    # (rows too long for the registers), and the row resident in 4, 8 or 16 pieces per thread, with 16384
-    # and 16392 on either side of a boundary between forms
     import oracle
-    if V in (12000, 16384, 16392) and (top_k or top_p < 1.0):
-        pytest.skip("resident-form shapes: the untruncated cases are enough")
-    if V == 256000 and (dtype == "f32" or top_k or top_p < 1.0 or temp != 1.0):
-        pytest.skip("large vocabulary: one plain case is enough")
     R = 24 if V > 100000 else 48
     stored = synth.gaussian_logits(R, V, sigma=3.0, seed=V + 5, dtype=dtype, ld=ld)
     rng = np.random.default_rng(V)
