@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations")
     ap.add_argument("--top-k", type=int, default=None, help="override the configuration's top_k (0 = off)")
     ap.add_argument("--top-p", type=float, default=None, help="override the configuration's top_p (1 = off)")
+    ap.add_argument("--logits", choices=["bf16", "f32"], default=None,
+                    help="storage type of the logits between the two kernels (default: the configuration's)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold (rotating buffers) kernel leg")
     ap.add_argument("--rows16x", action="store_true",
@@ -75,8 +77,9 @@ def main():
     if args.top_p is not None:
         top_p = args.top_p
     R = Bn * N
-    tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
-    esz = 2 if cfg["dtype"] == "bf16" else 4
+    ldt = args.logits or cfg["dtype"]
+    tdt = torch.bfloat16 if ldt == "bf16" else torch.float32
+    esz = 2 if ldt == "bf16" else 4
 
     def up(a):
         if a.dtype == np.uint16:
@@ -146,9 +149,9 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg['name']}: as_decode V={V} d={d} {cfg['dtype']} "
-                               f"weights+logits, B={Bn} N={N} (R={R}) T={T} temp={temp} top_k={top_k} "
+                               f"weights, {ldt} logits, B={Bn} N={N} (R={R}) T={T} temp={temp} top_k={top_k} "
                                f"top_p={top_p} eos={eos}; one step = one whole decode ({R * T} code-steps)",
-                   "storage": cfg["dtype"], "rows": R, "decode_steps": T,
+                   "storage": ldt, "rows": R, "decode_steps": T,
                    "value_with_dispatch_events": code_steps / (t3 - t2)},
         "roofline": {
             "kernel": ("threshold_resident_kernel with the sampling step fused (top-k rows), as launched inside "
