@@ -572,11 +572,17 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
             __syncthreads();
             // mass per coarse bin, in the fixed point of the radix path
             forget_row();
+            // A logit whose mass rounds to zero adds it to a slot of the lane's own instead of a bin: no
+            // branch per logit, and the many zeros of a peaked row do not pile onto the last bin.
+            typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+            lds_u64 *const bins = (lds_u64 *)sh.hist;
+            lds_u64 *const sink = (lds_u64 *)sh.mcount + (tid & 63);
             auto add_mass = [&](float x) __attribute__((always_inline)) {
                 const float y = fmaf(x, k, nr);
                 const float e = __builtin_amdgcn_exp2f(y);
                 const uint32_t q = (uint32_t)(e * 2147483648.f + 0.5f);
-                if (q) atomicAdd(&sh.hist[coarse_bin_nonpositive(y)], (unsigned long long)q);
+                lds_u64 *const dst = q ? bins + coarse_bin_nonpositive(y) : sink;
+                __hip_atomic_fetch_add(dst, (unsigned long long)q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             };
 #pragma unroll
             for (int p = 0; p < NP; ++p)
@@ -652,17 +658,25 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
                 }
             };
             // branch-free over the registers: which of this thread's pieces hold a logit of the bin
+            // (compares as wave-wide lane masks: two vector compares per logit, the and/or of the masks is
+            // scalar work)
+            auto bin_lanes = [&](uint32_t bits) __attribute__((always_inline)) {
+                const float x = __builtin_bit_cast(float, bits);
+                return __builtin_amdgcn_fcmpf(x, xlo, 3 /* ordered >= */) &
+                       __builtin_amdgcn_fcmpf(x, xhi, 4 /* ordered <  */);
+            };
+            const int lane_no = tid & 63;
             uint32_t hot = 0;
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
-                bool any = false;
+                uint64_t lanes = 0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t w = pc[p][i];
-                    if constexpr (kHalf) any |= in_bin(w << 16) | in_bin(w & 0xffff0000u);
-                    else any |= in_bin(w);
+                    if constexpr (kHalf) lanes |= bin_lanes(w << 16) | bin_lanes(w & 0xffff0000u);
+                    else lanes |= bin_lanes(w);
                 }
-                hot |= any ? 1u << p : 0u;
+                hot |= ((lanes >> lane_no) & 1u) ? 1u << p : 0u;
             }
             // those few pieces once more from memory (a loop over set bits cannot index registers), one body
             // of code for all of them
