@@ -478,22 +478,45 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
                 if constexpr (STEP) sh.cidx[i] = (uint32_t)v;
             }
         };
+        // Branch-free over the registers: which of this thread's pieces hold a key at or above the bound (the
+        // compares as wave-wide lane masks, their or is scalar work); those few pieces are then read once more
+        // from memory, in one loop, since a loop over set bits cannot index registers.
+        {
+            const int lane_no = tid & 63;
+            const uint32_t t = kHalf ? lkey << 16 : lkey;
+            uint32_t hot = 0;
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
+            for (int p = 0; p < NP; ++p) {
+                uint64_t lanes = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t w = pc[p][i];
-                const int32_t v0 = (p * kThreads + tid) * EPP;
-                if constexpr (kHalf) {
-                    const uint32_t t = lkey << 16;
-                    if (w >= t || (w << 16) >= t) {          // rare
-                        if ((w >> 16) >= lkey) candidate(w >> 16, v0 + 2 * i + 1);
-                        if ((w & 0xffffu) >= lkey) candidate(w & 0xffffu, v0 + 2 * i);
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = pc[p][i];
+                    lanes |= __builtin_amdgcn_uicmp(w, t, 35 /* unsigned >= */);
+                    if constexpr (kHalf) lanes |= __builtin_amdgcn_uicmp(w << 16, t, 35);
+                }
+                hot |= ((lanes >> lane_no) & 1u) ? 1u << p : 0u;
+            }
+            while (hot) {
+                const int p = __builtin_ctz(hot);
+                hot &= hot - 1;
+                const int32_t piece = p * kThreads + tid;
+                const u32x4 again = reinterpret_cast<const u32x4 *>(row)[piece];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = again[i];
+                    if constexpr (kHalf) {
+                        const int32_t v = piece * EPP + 2 * i;
+                        const uint32_t k0 = K::key((T)(w & 0xffffu)), k1 = K::key((T)(w >> 16));
+                        if (v < V && k0 >= lkey) candidate(k0, v);
+                        if (v + 1 < V && k1 >= lkey) candidate(k1, v + 1);
+                    } else {
+                        const int32_t v = piece * EPP + i;
+                        const uint32_t k0 = K::key(__builtin_bit_cast(float, w));
+                        if (v < V && k0 >= lkey) candidate(k0, v);
                     }
-                } else {
-                    if (w >= lkey) candidate(w, v0 + i);
                 }
             }
+        }
         __syncthreads();
         ncand = sh.ncand;
         if (ncand > (uint32_t)kCandCap) {
@@ -859,7 +882,69 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
             const uint32_t key = sh.ckey[c];
             const float e = key >= thr_key ? fast_exp2(fmaf(K::from_key(key), k, -ref)) : 0.f;
             sh.cq[c] = __builtin_bit_cast(uint32_t, e);
+            if (!(e > 0.f)) sh.cidx[c] = 0xffffffffu;       // not kept (or no weight): behind every real index
             part += (double)e;
+        }
+        if (ncand <= (uint32_t)kThreads) {
+            // The usual case, one candidate per thread: its rank among the kept ones by vocabulary index (the
+            // indices are distinct) is an integer loop; the weights go to their ranks, one fp64 scan gives
+            // every kept token the mass before it, and the bucket is the last one whose mass before it does
+            // not exceed c*S (past the end by rounding: the last kept token).
+            double *se = reinterpret_cast<double *>(sh.hist) + 16;           // [kThreads] weights by rank
+            uint32_t *sc = reinterpret_cast<uint32_t *>(se + kThreads);      // [kThreads] candidate at that rank
+            uint32_t *ured = sh.mcount;
+            __syncthreads();
+            const bool have = (uint32_t)tid < ncand;
+            const float e_mine = have ? __builtin_bit_cast(float, sh.cq[tid]) : 0.f;
+            const uint32_t idx = have ? sh.cidx[tid] : 0xffffffffu;
+            uint32_t rank = 0, nk = 0;
+            for (uint32_t j = 0; j < ncand; ++j) {
+                const uint32_t o = sh.cidx[j];
+                rank += o < idx ? 1u : 0u;
+                nk += o != 0xffffffffu ? 1u : 0u;
+            }
+            if (idx != 0xffffffffu) {
+                se[rank] = (double)e_mine;
+                sc[rank] = (uint32_t)tid;
+            }
+            __syncthreads();
+            const double v = (uint32_t)tid < nk ? se[tid] : 0.0;
+            const double incl = wave_scan_add(v);
+            if ((tid & 63) == 63) dred[tid >> 6] = incl;
+            __syncthreads();
+            double base = 0.0, S = 0.0;
+#pragma unroll
+            for (int w = 0; w < kThreads / 64; ++w) {
+                const double t = dred[w];
+                if (w < (tid >> 6)) base += t;
+                S += t;
+            }
+            const double tau = (double)sa.codes[r] * S;
+            const double lo = base + incl - v;
+            const uint32_t best = ((uint32_t)tid < nk && lo <= tau) ? (uint32_t)tid + 1u : 0u;
+            const uint32_t wbest = wave_reduce_umax(best);
+            if ((tid & 63) == 0) ured[tid >> 6] = wbest;
+            __syncthreads();
+            uint32_t gbest = ured[0];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) gbest = gbest > ured[w] ? gbest : ured[w];
+            if (best == gbest && gbest != 0u) {
+                RowOut o;
+                o.token = (int32_t)sh.cidx[sc[tid]];
+                o.c_next = rescale_code(tau, lo, v);
+                o.prob = (float)(v / S);
+                o.f_lo = (float)(lo / S);
+                write_row(sa, r, o);
+            } else if (gbest == 0u && tid == 0) {
+                // no kept candidate with weight: cannot happen for finite logits; leave a valid row behind
+                RowOut o;
+                o.token = 0;
+                o.c_next = rescale_code(0.0, 0.0, 1.0);
+                o.prob = 0.f;
+                o.f_lo = 0.f;
+                write_row(sa, r, o);
+            }
+            return;
         }
         part = wave_sum(part);
         if ((tid & 63) == 0) dred[tid >> 6] = part;
