@@ -112,6 +112,9 @@ def test_step_is_deterministic_and_in_place():
 def test_step_truncation(dtype, top_k, top_p, temp):
     _check(32128, 64, dtype, temp=temp, top_k=top_k, top_p=top_p, seed=31)
     _check(1001, 40, dtype, temp=temp, top_k=min(top_k, 900), top_p=top_p, seed=32)
+    # rows that take the register-resident kernels and end inside a 16-byte piece (the padding holds +1e30)
+    _check(1001, 40, dtype, temp=temp, top_k=top_k, top_p=top_p, ld=1008, seed=37)
+    _check(4099, 24, dtype, temp=temp, top_k=top_k, top_p=top_p, ld=4104, seed=38)
 
 
 @pytest.mark.parametrize("top_k,top_p", [(40, 1.0), (0, 0.9), (5, 0.5)])
