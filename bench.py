@@ -17,6 +17,7 @@ Prints ONE JSON line: whole-job code-steps/s, plus
                 16x the rows (1 GiB)
   fused_decode  the decode without the logits round trip (as_decode_fused)
   encode        the encode direction over the decoded sequences (as_encode)
+  ancestral     the ancestral-sampling mode and the lattice estimator
   logits_gemm   the MFMA logits kernel: achieved TFLOP/s against the bf16 peak
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on a bounded
                 sample of the same workload
@@ -231,6 +232,31 @@ def main():
         "code_steps_per_s_with_dispatch_events": code_steps / args.steps * 3 / (e1 - e0)}
     if out["encode"]["achieved"]:
         out["encode"]["frac"] = out["encode"]["achieved"] / HBM_PEAK_GBS
+
+    # ---- ancestral mode (fresh uniforms per step, same kernels) and the lattice estimator over the decoded batch
+    uniforms = torch.from_numpy(synth.uniform_codes(T * R, seed=6)).cuda()
+    tokens_a = torch.empty_like(tokens)
+    B.as_decode_ancestral(ctx, model, prompts, N, T, uniforms, temp, top_k, top_p, eos, tokens_a)
+    torch.cuda.synchronize()
+    a0 = time.perf_counter()
+    for _ in range(3):
+        B.as_decode_ancestral(ctx, model, prompts, N, T, uniforms, temp, top_k, top_p, eos, tokens_a)
+    torch.cuda.synchronize()
+    a1 = time.perf_counter()
+    score = torch.linspace(0.0, 1.0, V, dtype=torch.float32, device="cuda")
+    est = torch.empty(Bn, dtype=torch.float64, device="cuda")
+    B.as_estimate_mean(ctx, tokens, score, eos, est)
+    torch.cuda.synchronize()
+    m0 = time.perf_counter()
+    for _ in range(20):
+        B.as_estimate_mean(ctx, tokens, score, eos, est)
+    torch.cuda.synchronize()
+    m1 = time.perf_counter()
+    out["ancestral"] = {
+        "what": "as_decode_ancestral (the caller's uniforms[t, r] as codes, kernels unchanged); as_estimate_mean "
+                "over the lattice decode's tokens (additive per-token score, fp64, one value per prompt)",
+        "value": code_steps / args.steps * 3 / (a1 - a0), "unit": "code-steps/s",
+        "estimate_mean_us_per_call": (m1 - m0) / 20 * 1e6}
 
     if args.copy_calibration:
         src_t = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda").random_()
