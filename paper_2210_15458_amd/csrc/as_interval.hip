@@ -114,17 +114,26 @@ struct ResidentRow {
     }
 };
 
-// block-wide sum in a fixed order: lanes by the wave scan, then the waves in index order
-__device__ __forceinline__ double block_sum(double x, double *scratch)
+// three block-wide sums at once, each in a fixed order: lanes by the wave scan, then the waves in index order
+__device__ __forceinline__ void block_sum3(double &a, double &b, double &c, double *scratch)
 {
-    x = wave_sum(x);
+    a = wave_sum(a);
+    b = wave_sum(b);
+    c = wave_sum(c);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        scratch[wave] = a;
+        scratch[kThreads / 64 + wave] = b;
+        scratch[2 * (kThreads / 64) + wave] = c;
+    }
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = x;
-    __syncthreads();
-    double t = 0.0;
+    a = b = c = 0.0;
 #pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) t += scratch[w];
-    return t;
+    for (int w = 0; w < kThreads / 64; ++w) {
+        a += scratch[w];
+        b += scratch[kThreads / 64 + w];
+        c += scratch[2 * (kThreads / 64) + w];
+    }
 }
 
 // MODE 0: element by element; 1: 16-byte pieces, two passes over memory; 4, 8, 16: the row fits in that
@@ -133,7 +142,7 @@ template <class T, int MODE>
 __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
 {
     constexpr bool RES = MODE >= 4;
-    __shared__ double scratch[kThreads / 64];
+    __shared__ double scratch[3 * (kThreads / 64)];
     __shared__ float fscratch[kThreads / 64];
     const int64_t r = blockIdx.x;
     const int32_t tok = a.tokens[r * a.tok_stride];
@@ -215,9 +224,7 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
             before += (double)s_before;
         }
     });
-    all = block_sum(all, scratch);
-    before = block_sum(before, scratch);
-    at = block_sum(at, scratch);
+    block_sum3(all, before, at, scratch);
     if (threadIdx.x == 0) {
         // a token outside the vocabulary or outside the kept set has probability zero
         const double f_lo = all > 0.0 ? before / all : 0.0;
