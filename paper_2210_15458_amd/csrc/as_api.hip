@@ -113,7 +113,6 @@ as_status as_ctx_create(as_ctx **out, int64_t max_rows, int32_t V, as_dtype logi
     if (const char *shape = getenv("AS_STEP_SHAPE")) c->step_shape = atoi(shape);
     if (const char *shape = getenv("AS_GEMM_SHAPE")) c->gemm_shape = atoi(shape);
     if (const char *path = getenv("AS_THR_PATH")) c->thr_path = atoi(path);
-    if (const char *path = getenv("AS_INTERVAL_PATH")) c->interval_path = atoi(path);
     if (const char *gm = getenv("AS_GEMM_GM")) c->gemm_gm = atoi(gm);
     e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
     if (e != hipSuccess) {

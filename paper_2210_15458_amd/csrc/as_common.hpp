@@ -56,7 +56,6 @@ struct as_ctx {
     int gemm_shape = 0;            // logits kernel choice (tuning knob: 0 = persistent where it applies, 1 = tile kernel)
     int thr_path = 0;              // keep-threshold kernel choice (tuning knob: 0 = resident where it applies, 1 = radix)
     int gemm_gm = 0;               // logits kernel, many row tiles: workers of an XCD along the rows (tuning knob: 0 = default)
-    int interval_path = 0;         // encode kernel choice (tuning knob: 0 = row in registers where it fits, 1 = two passes)
     int num_cus = 0;               // compute units of the device (the persistent logits kernel runs one block on each)
     std::string err;
 };

@@ -65,55 +65,6 @@ __device__ __forceinline__ void for_row(const T *row, int32_t V, G g)
     }
 }
 
-// The same visit over a row that one pass of 16-byte loads has left in registers: piece u*kThreads + thread of
-// the row sits in w[u], so a thread meets its pieces in the order for_row gives them.
-template <class T, int NP>
-struct ResidentRow {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    static constexpr int EPP = 16 / (int)sizeof(T);
-    u32x4 w[NP];
-
-    __device__ __forceinline__ void load(const T *row, int32_t V)
-    {
-        const int32_t npieces = (V + EPP - 1) / EPP;
-#pragma unroll
-        for (int u = 0; u < NP; ++u) {
-            const int32_t piece = u * kThreads + (int32_t)threadIdx.x;
-            w[u] = piece < npieces ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + piece)
-                                   : u32x4{0, 0, 0, 0};
-        }
-    }
-    // between two visits: the compiler must not carry the unpacked values of one over to the next, or the
-    // row is held twice
-    __device__ __forceinline__ void forget()
-    {
-#pragma unroll
-        for (int u = 0; u < NP; ++u) asm volatile("" : "+v"(w[u]));
-    }
-    template <class G>
-    __device__ __forceinline__ void visit(int32_t V, G g) const
-    {
-#pragma unroll
-        for (int u = 0; u < NP; ++u) {
-            const int32_t v0 = (u * kThreads + (int32_t)threadIdx.x) * EPP;
-            if (v0 >= V) break;
-            float x[EPP];
-#pragma unroll
-            for (int e = 0; e < EPP; ++e) {
-                if constexpr (sizeof(T) == 2) {
-                    const uint32_t word = w[u][e >> 1];
-                    x[e] = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
-                } else {
-                    const uint32_t word = w[u][e];
-                    x[e] = __builtin_bit_cast(float, word);
-                }
-            }
-            const int n = V - v0 < EPP ? V - v0 : EPP;
-            g(v0, x, n, std::integral_constant<int, EPP>{});
-        }
-    }
-};
-
 // three block-wide sums at once, each in a fixed order: lanes by the wave scan, then the waves in index order
 __device__ __forceinline__ void block_sum3(double &a, double &b, double &c, double *scratch)
 {
@@ -136,12 +87,11 @@ __device__ __forceinline__ void block_sum3(double &a, double &b, double &c, doub
     }
 }
 
-// MODE 0: element by element; 1: 16-byte pieces, two passes over memory; 4, 8, 16: the row fits in that
-// many pieces per thread and is read once (the arithmetic and its order are the same in all of them).
-template <class T, int MODE>
+// VEC: rows are read in 16-byte pieces (else element by element).  One pass over memory: every thread keeps an
+// integer reference that follows the largest logit it has seen (see below).
+template <class T, bool VEC>
 __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
 {
-    constexpr bool RES = MODE >= 4;
     __shared__ double scratch[3 * (kThreads / 64)];
     __shared__ float fscratch[kThreads / 64];
     const int64_t r = blockIdx.x;
@@ -159,12 +109,7 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
     const float thr = a.thr ? a.thr[r] : -__builtin_inff();
     const float k = a.k;
 
-    ResidentRow<T, RES ? MODE : 1> res;
-    if constexpr (RES) res.load(row, a.V);
-    auto each_run = [&](auto g) __attribute__((always_inline)) {
-        if constexpr (RES) res.visit(a.V, g);
-        else for_row<T, MODE == 1>(row, a.V, g);
-    };
+    auto each_run = [&](auto g) __attribute__((always_inline)) { for_row<T, VEC>(row, a.V, g); };
 
     // a run as the sums see it: what is cut off by the threshold or lies past the row's end counts as -inf
     // (weight exactly 0); whole runs of an untruncated row, nearly all of them, pass through untouched
@@ -180,30 +125,12 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
         }
     };
 
-    float m = -__builtin_inff();
-    each_run([&](int32_t, const float *x, int n, auto cap) __attribute__((always_inline)) {
-        constexpr int E = decltype(cap)::value;
-        float y[E];
-        kept(x, n, cap, y);
-#pragma unroll
-        for (int e = 0; e < E; ++e) m = fmaxf(m, y[e]);
-    });
-    if constexpr (RES) res.forget();
-    m = wave_max(m);
-    if ((threadIdx.x & 63) == 0) fscratch[threadIdx.x >> 6] = m;
-    __syncthreads();
-    m = fscratch[0];
-#pragma unroll
-    for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fscratch[w]);
-    const float nref = -fmaxf(ceilf(m * k), -100000.f);
-
     // per run: fp32 sum of its (at most 8) weights in order, then one fp64 add per total; only the one run
     // that holds the token looks at single weights
     double all = 0.0, before = 0.0, at = 0.0;
-    each_run([&](int32_t v0, const float *x, int n, auto cap) __attribute__((always_inline)) {
+    auto add_run = [&](int32_t v0, const float *y, float nref, auto cap) __attribute__((always_inline)) {
         constexpr int E = decltype(cap)::value;
-        float y[E], w[E];
-        kept(x, n, cap, y);
+        float w[E];
         float s_all = 0.f;
 #pragma unroll
         for (int e = 0; e < E; ++e) {
@@ -223,7 +150,38 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
             }
             before += (double)s_before;
         }
-    });
+    };
+    {
+        // One pass over memory: every thread keeps an integer reference that follows the largest logit it has
+        // seen; when it rises, what the thread has summed so far shrinks by an exact power of two.  At the end
+        // the threads are brought to the block's reference the same way.
+        float ref = -100000.f;
+        auto rescale = [&](float to) __attribute__((always_inline)) {
+            const int down = (int)fmaxf(ref - to, -2000.f);
+            all = ldexp(all, down);
+            before = ldexp(before, down);
+            at = ldexp(at, down);
+            ref = to;
+        };
+        each_run([&](int32_t v0, const float *x, int n, auto cap) __attribute__((always_inline)) {
+            constexpr int E = decltype(cap)::value;
+            float y[E];
+            kept(x, n, cap, y);
+            float pm = y[0];
+#pragma unroll
+            for (int e = 1; e < E; ++e) pm = fmaxf(pm, y[e]);
+            const float want = fmaxf(ceilf(pm * k), ref);
+            if (want > ref) rescale(want);
+            add_run(v0, y, -ref, cap);
+        });
+        float top = wave_max(ref);
+        if ((threadIdx.x & 63) == 0) fscratch[threadIdx.x >> 6] = top;
+        __syncthreads();
+        top = fscratch[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) top = fmaxf(top, fscratch[w]);
+        rescale(top);
+    }
     block_sum3(all, before, at, scratch);
     if (threadIdx.x == 0) {
         // a token outside the vocabulary or outside the kept set has probability zero
@@ -256,20 +214,13 @@ as_status launch_interval(as_ctx *ctx, const IntervalArgs &a)
     const size_t esz = a.dtype == AS_BF16 ? 2 : 4;
     const bool vec = reinterpret_cast<uintptr_t>(a.logits) % 16 == 0 && (a.ld * esz) % 16 == 0;
     const dim3 grid((unsigned)a.rows), block(kThreads);
-    // pieces per thread when the whole row is to stay in registers (at most 16: 64 registers)
-    const int64_t per_thread = ((int64_t)a.V * (int64_t)esz + 16 * kThreads - 1) / (16 * kThreads);
-    const int mode = !vec ? 0 : ctx->interval_path == 1 || per_thread > 16 ? 1 : per_thread <= 4 ? 4
-                                                                             : per_thread <= 8 ? 8 : 16;
-#define AS_INTERVAL_LAUNCH(T)                                                                          \
-    switch (mode) {                                                                                    \
-    case 0: launch(ctx, kKernelInterval, interval_kernel<T, 0>, grid, block, 0, a); break;             \
-    case 1: launch(ctx, kKernelInterval, interval_kernel<T, 1>, grid, block, 0, a); break;             \
-    case 4: launch(ctx, kKernelInterval, interval_kernel<T, 4>, grid, block, 0, a); break;             \
-    case 8: launch(ctx, kKernelInterval, interval_kernel<T, 8>, grid, block, 0, a); break;             \
-    default: launch(ctx, kKernelInterval, interval_kernel<T, 16>, grid, block, 0, a); break;           \
+    if (a.dtype == AS_BF16) {
+        if (vec) launch(ctx, kKernelInterval, interval_kernel<uint16_t, true>, grid, block, 0, a);
+        else launch(ctx, kKernelInterval, interval_kernel<uint16_t, false>, grid, block, 0, a);
+    } else {
+        if (vec) launch(ctx, kKernelInterval, interval_kernel<float, true>, grid, block, 0, a);
+        else launch(ctx, kKernelInterval, interval_kernel<float, false>, grid, block, 0, a);
     }
-    if (a.dtype == AS_BF16) { AS_INTERVAL_LAUNCH(uint16_t) } else { AS_INTERVAL_LAUNCH(float) }
-#undef AS_INTERVAL_LAUNCH
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }

@@ -31,10 +31,9 @@ def _interval_step(stored, tokens, V, temp=1.0, top_k=0, top_p=1.0, finished=Non
 
 
 _MODS = [(1.0, 0, 1.0), (0.7, 0, 1.0), (1.0, 40, 1.0), (1.0, 0, 0.9)]
-# every form of the kernel: element by element (odd strides), two passes over memory (rows too long for the
-# registers), and the row resident in 4, 8 or 16 pieces per thread, with 16384 and 16392 on either side of a
-# boundary between forms.  All logit modifiers on the general shapes, the untruncated ones on the
-# resident-form shapes, one plain case on the large vocabulary.
+# both forms of the kernel (element by element for odd strides, 16-byte pieces otherwise), rows shorter than a
+# block's one sweep and rows of many sweeps, every logit modifier on the general shapes, the untruncated ones
+# on three more lengths, one plain case on the large vocabulary
 _INTERVAL_CASES = (
     [(dt, V, ld, *m) for dt in ("bf16", "f32") for (V, ld) in [(32128, None), (1001, None), (1001, 1008), (5, None)]
      for m in _MODS]
@@ -62,14 +61,6 @@ def test_interval_step_matches_oracle(dtype, V, ld, temp, top_k, top_p):
             continue                                   # kept set itself is a coin toss at the nucleus boundary
         assert abs(w[r] - w0[r] * p[r]) <= REL * w0[r] * p[r] + 1e-300, (r, w[r], w0[r] * p[r])
         assert abs(lo[r] - (lo0[r] + w0[r] * f_lo[r])) <= w0[r] * ABS_F + 1e-15, (r, lo[r], f_lo[r])
-
-
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_interval_step_two_pass_form(dtype, monkeypatch):
-    # the two-pass form on a row that would otherwise stay in registers
-    monkeypatch.setenv("AS_INTERVAL_PATH", "1")
-    test_interval_step_matches_oracle(dtype, 12000, None, 0.7, 0, 1.0)
-    test_interval_step_matches_oracle(dtype, 1001, 1008, 1.0, 40, 1.0)
 
 
 def test_interval_step_finished_rows_and_bad_tokens():
