@@ -71,7 +71,10 @@ def compare_step(gpu, ref, V, label="", trunc=False):
     assert not bad.any(), (f"{label}: {bad.sum()} token mismatches away from any boundary; first rows "
                            f"{np.nonzero(bad)[0][:5]}, gpu {tok_g[bad][:5]}, oracle {tok_o[bad][:5]}, "
                            f"delta {ref['delta'][bad][:5]}")
-    ok = ~mism
+    # rows whose nucleus closes within the band of top_p may keep one group more or less than the oracle: their
+    # tokens are excused above, and their probabilities and codes are not comparable either (another kept set
+    # is another normalisation); they are counted below
+    ok = ~mism & ~nuc
     p = ref["p"][ok]
     rel_p = np.abs(gpu["p"][ok] - p) / p
     assert np.all(rel_p <= 1e-5), f"{label}: probability off by {rel_p.max():.3g} relative"
@@ -85,7 +88,7 @@ def compare_step(gpu, ref, V, label="", trunc=False):
         assert np.array_equal(gpu["finished"][ok], ref["finished"][ok])
     strict = dc <= 1e-5 * np.maximum(ref["c_next"][ok], 1e-30) + 2.0 ** -24
     return dict(rows=len(tok_o), mismatches=int(mism.sum()), boundary=int((mism & near).sum()),
-                nucleus=int((mism & nuc & ~near).sum()), in_band=int(near.sum()),
+                nucleus=int((mism & nuc & ~near).sum()), nucleus_rows=int(np.sum(nuc)), in_band=int(near.sum()),
                 code_within_1e5_rel=float(strict.mean()), worst_dc_times_p=float((dc * p).max(initial=0.0)),
                 worst_rel_p=float(rel_p.max(initial=0.0)))
 
