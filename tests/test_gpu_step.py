@@ -152,6 +152,21 @@ def test_step_truncation_hard_rows(dtype):
         print("   ", compare_step(gpu, ref, V, label, trunc=True), flush=True)
 
 
+@pytest.mark.parametrize("V,dtype", [(V, dt) for V in (7, 64, 255, 4097, 50257, 100003) for dt in ("bf16", "f32")
+                                     if not (V > 60000 and dt == "f32")])
+def test_step_shape_sweep(V, dtype):
+    """Vocabulary sizes around the kernels' internal limits (one vector, one chunk, one share, one tile, several
+    tiles, beyond what the register-resident kernels take), with and without row padding, flat and peaked rows,
+    every kind of logit modifier."""
+    rng = np.random.default_rng(V * 2 + (dtype == "f32"))
+    for temp, k, p in [(1.0, 0, 1.0), (0.3, 0, 1.0), (2.5, 0, 1.0), (1.0, 40, 1.0), (0.8, 0, 0.92), (1.2, 100, 0.5),
+                       (0.7, 128, 0.99)]:
+        for pad in (0, 8):
+            ld = None if pad == 0 else (V + 7) // 8 * 8 + pad
+            _check(V, 12 if V > 20000 else 24, dtype, temp=temp, top_k=min(k, V - 1), top_p=p, ld=ld,
+                   sigma=float(rng.choice([0.5, 3.0, 8.0])), seed=int(rng.integers(1, 1 << 30)))
+
+
 def test_step_truncation_multi_tile():
     _check(256000, 6, "bf16", top_k=40, seed=33)
     _check(256000, 6, "bf16", top_p=0.9, seed=34)
