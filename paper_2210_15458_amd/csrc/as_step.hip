@@ -150,9 +150,10 @@ struct SumRef {
 };
 
 // ===========================================================================
-// fast kernel: rows start on 16 bytes and hold a whole number of vectors
+// fast kernel: rows start on 16 bytes and are padded to whole vectors (the last vector of a row may be partial)
 // ===========================================================================
-template <int DT, int NW, int ITERS, int OCC, bool HAS_THR>
+// PARTIAL: the row's length is not a whole number of vectors (its last vector is padded out by the row stride)
+template <int DT, int NW, int ITERS, int OCC, bool HAS_THR, bool PARTIAL>
 __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntiles)
 {
     using T = typename Elem<DT>::T;
@@ -184,7 +185,8 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
     const int64_t src = a.row_ids ? (int64_t)a.row_ids[r] : r;
     const unsigned char *rowb =
         reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.logits) + src * a.ld);
-    const int32_t nvec = a.V / EPV;
+    const int32_t nvec = (a.V + EPV - 1) / EPV;   // the last vector may be partial: rem of its elements are the row's
+    const int32_t rem = PARTIAL ? a.V % EPV : 0;
     const float k = a.k;
     float thr = 0.f;
     if constexpr (HAS_THR) thr = a.thr[r];
@@ -205,10 +207,12 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
         const unsigned char *base = rowb + (size_t)v0 * 16u;
         int32_t mych = ITERS;                                   // chunks of the share in which this lane is inside the row
         uint32_t off_last = 0;
+        uint32_t tail_off = 0;                                  // where the row's partial last vector sits in the share
         if constexpr (RAGGED) {
             mych = (nvec - v0 - lane + 63) >> 6;
             mych = mych < 0 ? 0 : (mych > ITERS ? ITERS : mych);
             off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
+            if constexpr (PARTIAL) tail_off = (uint32_t)(nvec - 1 - v0) * 16u;
         }
         // A wave issues in order: while a load waits for room in the memory pipeline the wave
         // cannot start on data it already has.  So only AHEAD groups are requested up front
@@ -240,6 +244,17 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
                 if constexpr (HAS_THR) {
 #pragma unroll
                     for (int i = 0; i < EPV; ++i) x[jj][i] = (x[jj][i] >= thr) ? x[jj][i] : -__builtin_inff();
+                }
+                if constexpr (RAGGED && PARTIAL) {
+                    if (rem != 0) {
+                        // what follows the row in its partial last vector is no logit; lanes past the row's end
+                        // may have re-read that vector too
+                        uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                        off = off < off_last ? off : off_last;
+                        const bool part = off == tail_off;
+#pragma unroll
+                        for (int i = 0; i < EPV; ++i) x[jj][i] = (part && i >= rem) ? -__builtin_inff() : x[jj][i];
+                    }
                 }
                 m[jj] = vec_max<EPV>(x[jj]);
             }
@@ -286,7 +301,8 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
         for (int t = t_begin; t < t_end; ++t) {
             const int32_t v0 = t * kTile + wave * kShare;
             SumRef wr{0.f, kRefFloor};
-            if (v0 + kShare <= nvec) wr = stream(v0, std::false_type{});
+            // (a share that ends exactly with the row still takes the ragged form if the row's last vector is partial)
+            if (v0 + kShare < nvec || (v0 + kShare == nvec && rem == 0)) wr = stream(v0, std::false_type{});
             else if (v0 < nvec) wr = stream(v0, std::true_type{});
             else {
                 // a share wholly past the row end.  (The vectors are overwritten too so that the
@@ -440,10 +456,12 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
     float x[EPV];
     unpack<DT>(hv, x);
     double ed[EPV];
+    const bool partial = PARTIAL && rem != 0 && (int64_t)ts * kTile + (int64_t)wave * kShare + (int64_t)cj * 64 + lane == nvec - 1;
 #pragma unroll
     for (int i = 0; i < EPV; ++i) {
         float e = fast_exp2(fmaf(x[i], k, -rh));
         if constexpr (HAS_THR) e = (x[i] >= thr) ? e : 0.f;
+        if (partial && i >= rem) e = 0.f;
         ed[i] = (double)ldexpf(e, shf);
     }
     double acc = incl2 - lv;
@@ -499,13 +517,17 @@ template <int DT, int NW, int ITERS, int OCC, bool HAS_THR>
 as_status launch_shape(as_ctx *ctx, const StepArgs &a)
 {
     constexpr int EPV = Elem<DT>::kPerVec;
-    const int64_t nvec = a.V / EPV;
+    const int64_t nvec = ((int64_t)a.V + EPV - 1) / EPV;
     const int64_t tile = (int64_t)NW * ITERS * 64;
     const int ntiles = (int)((nvec + tile - 1) / tile);
     const size_t lds = ((size_t)NW * ITERS * 64 + (size_t)ntiles * NW * 2) * sizeof(float);
     if (lds > 60 * 1024) return fail(ctx, AS_ERR_UNSUPPORTED, "vocabulary too large for the share table");
-    launch(ctx, kKernelStep, step_kernel<DT, NW, ITERS, OCC, HAS_THR>, dim3((unsigned)a.rows), dim3(NW * 64), lds, a,
-           ntiles);
+    if (a.V % EPV != 0)
+        launch(ctx, kKernelStep, step_kernel<DT, NW, ITERS, OCC, HAS_THR, true>, dim3((unsigned)a.rows), dim3(NW * 64),
+               lds, a, ntiles);
+    else
+        launch(ctx, kKernelStep, step_kernel<DT, NW, ITERS, OCC, HAS_THR, false>, dim3((unsigned)a.rows), dim3(NW * 64),
+               lds, a, ntiles);
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }
@@ -526,10 +548,9 @@ as_status launch_fast(as_ctx *ctx, const StepArgs &a)
 template <int DT>
 as_status launch_dt(as_ctx *ctx, const StepArgs &a)
 {
-    constexpr int EPV = Elem<DT>::kPerVec;
     const size_t esz = (DT == AS_BF16) ? 2 : 4;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.logits) % 16 == 0) && ((a.ld * esz) % 16 == 0);
-    if (aligned && a.V % EPV == 0 && ctx->step_shape != 9)
+    if (aligned && ctx->step_shape != 9)
         return a.thr ? launch_fast<DT, true>(ctx, a) : launch_fast<DT, false>(ctx, a);
     if (a.thr) launch(ctx, kKernelStep, step_generic_kernel<DT, true>, dim3((unsigned)a.rows), dim3(256), 0, a);
     else launch(ctx, kKernelStep, step_generic_kernel<DT, false>, dim3((unsigned)a.rows), dim3(256), 0, a);
