@@ -988,6 +988,241 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
     }
 }
 
+
+// ------------------------------------------------------------ streamed path
+//
+// Rows too long for the registers (more than 32768 logits), readable in 16-byte pieces, k at most half the
+// thread count: the method of the resident kernel with every visit of the row a pass over memory, four pieces
+// per thread in flight.  Top-k takes two passes (thread maxima, then the logits at or above the bound they
+// give), the nucleus alone three (maximum, mass per coarse bin, the logits of the bin where the nucleus
+// closes); the nucleus after top-k works on the candidate table.  Same keys, same fixed-point masses, same
+// fall-back as the other two kernels, so the same threshold.
+template <int DT, bool HAS_K, bool HAS_P>
+__global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *logits, int64_t ld, int32_t V,
+                                                                    const uint8_t *finished_in,
+                                                                    const int32_t *row_ids, float temp,
+                                                                    int32_t top_k, float top_p, float *thr_out)
+{
+    using K = Key<DT>;
+    using T = typename K::T;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr bool kHalf = sizeof(T) == 2;
+    constexpr int EPP = 16 / (int)sizeof(T);
+    __shared__ Scratch sc;
+    Resident &sh = sc.res;
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    if (finished_in != nullptr && finished_in[r] != 0) return;
+    const int64_t src = row_ids ? (int64_t)row_ids[r] : r;
+    const T *row = reinterpret_cast<const T *>(logits) + src * ld;
+    const int32_t npieces = (V + EPP - 1) / EPP;
+
+    // f(key, value) for every logit of the row (value: the stored logit widened to fp32), each once
+    auto sweep = [&](auto f) __attribute__((always_inline)) {
+        for (int32_t base = tid; base < npieces; base += 4 * kThreads) {
+            u32x4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int32_t piece = base + u * kThreads;
+                w[u] = piece < npieces ? reinterpret_cast<const u32x4 *>(row)[piece] : u32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int32_t piece = base + u * kThreads;
+                if (piece >= npieces) break;
+                const int32_t live = V - piece * EPP;              // logits of the row in this piece (>= EPP: all)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t d = w[u][i];
+                    if constexpr (kHalf) {
+                        if (2 * i < live) f(K::key((T)(d & 0xffffu)), __builtin_bit_cast(float, d << 16));
+                        if (2 * i + 1 < live) f(K::key((T)(d >> 16)), __builtin_bit_cast(float, d & 0xffff0000u));
+                    } else {
+                        if (i < live) f(K::key(__builtin_bit_cast(float, d)), __builtin_bit_cast(float, d));
+                    }
+                }
+            }
+        }
+    };
+    auto umax = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
+
+    uint32_t thr_key = 0;
+    bool fall = false;
+    uint32_t ncand = 0;
+
+    if (HAS_K) {
+        // the k-th largest of the thread maxima bounds the k-th largest logit from below
+        uint32_t tmax = 0;
+        sweep([&](uint32_t key, float) __attribute__((always_inline)) { tmax = umax(tmax, key); });
+        sh.mcount[tid] = 0;
+        if (tid == 0) sh.ncand = 0;
+        uint32_t hi = wave_reduce_umax(tmax), lo = wave_reduce_umin(tmax);
+        uint32_t *red = reinterpret_cast<uint32_t *>(sh.hist);
+        if ((tid & 63) == 0) { red[tid >> 6] = hi; red[4 + (tid >> 6)] = lo; }
+        __syncthreads();
+        hi = red[0]; lo = red[4];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) { hi = umax(hi, red[w]); lo = red[4 + w] < lo ? red[4 + w] : lo; }
+        const float scale = 256.f / ((float)(hi - lo) + 1.f);
+        int mb = (int)((float)(hi - tmax) * scale);
+        mb = mb > kThreads - 1 ? kThreads - 1 : mb;
+        atomicAdd(&sh.mcount[mb], 1u);
+        __syncthreads();
+        unsigned long long total;
+        const unsigned long long mine = sh.mcount[tid];
+        const unsigned long long excl = block_excl_scan(mine, sh.wave_tot, total);
+        if (excl < (unsigned long long)top_k && excl + mine >= (unsigned long long)top_k) sh.pick = (uint32_t)tid;
+        if (tid == 0) sh.lkey = 0xffffffffu;
+        __syncthreads();
+        uint32_t l = mb <= (int)sh.pick ? tmax : 0xffffffffu;
+        l = wave_reduce_umin(l);
+        if ((tid & 63) == 0) atomicMin(&sh.lkey, l);
+        __syncthreads();
+        const uint32_t lkey = sh.lkey;
+        sweep([&](uint32_t key, float) __attribute__((always_inline)) {
+            if (key >= lkey) {
+                const uint32_t i = atomicAdd(&sh.ncand, 1u);
+                if (i < (uint32_t)kCandCap) sh.ckey[i] = key;
+            }
+        });
+        __syncthreads();
+        ncand = sh.ncand;
+        if (ncand > (uint32_t)kCandCap) {
+            fall = true;
+        } else {
+            for (uint32_t c = tid; c < ncand; c += kThreads) {
+                const uint32_t my = sh.ckey[c];
+                uint32_t ahead = 0;
+                for (uint32_t j = 0; j < ncand; ++j) {
+                    const uint32_t o = sh.ckey[j];
+                    ahead += (o > my || (o == my && j < c)) ? 1u : 0u;
+                }
+                if (ahead == (uint32_t)top_k - 1u) sh.pick = my;
+            }
+            __syncthreads();
+            thr_key = sh.pick;
+        }
+        __syncthreads();
+    }
+
+    if (HAS_P && !fall) {
+        const float k = 1.44269504088896340736f / temp;
+        double need;
+        unsigned long long before = 0;
+        if (HAS_K) {
+            // every survivor of top-k is in the candidate table
+            float m = -__builtin_inff();
+            for (uint32_t c = tid; c < ncand; c += kThreads)
+                if (sh.ckey[c] >= thr_key) m = fmaxf(m, K::from_key(sh.ckey[c]));
+            m = wave_max(m);
+            float *fred = reinterpret_cast<float *>(sh.hist);
+            if ((tid & 63) == 0) fred[tid >> 6] = m;
+            __syncthreads();
+            m = fred[0];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
+            const float nr = -fmaxf(ceilf(m * k), -100000.f);
+            unsigned long long local = 0, total;
+            for (uint32_t c = tid; c < ncand; c += kThreads) {
+                const uint32_t key = sh.ckey[c];
+                const unsigned long long q = key >= thr_key ? mass_q(K::from_key(key), k, nr) : 0ull;
+                sh.cq[c] = (uint32_t)q;
+                local += q;
+            }
+            block_excl_scan(local, sh.wave_tot, total);
+            need = (double)top_p * (double)total;
+            __syncthreads();
+        } else {
+            float m = -__builtin_inff();
+            sweep([&](uint32_t, float x) __attribute__((always_inline)) { m = fmaxf(m, x); });
+            m = wave_max(m);
+            float *fred = reinterpret_cast<float *>(sh.ckey);
+            if ((tid & 63) == 0) fred[tid >> 6] = m;
+            for (int b = tid; b < kCoarseBins; b += kThreads) sh.hist[b] = 0;
+            if (tid == 0) sh.ncand = 0;
+            __syncthreads();
+            m = fred[0];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
+            const float nr = -fmaxf(ceilf(m * k), -100000.f);
+            __syncthreads();
+            typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+            lds_u64 *const bins = (lds_u64 *)sh.hist;
+            lds_u64 *const sink = (lds_u64 *)sh.mcount + (tid & 63);
+            sweep([&](uint32_t, float x) __attribute__((always_inline)) {
+                const float y = fmaf(x, k, nr);
+                const float e = __builtin_amdgcn_exp2f(y);
+                const uint32_t q = (uint32_t)(e * 2147483648.f + 0.5f);
+                lds_u64 *const dst = q ? bins + coarse_bin_nonpositive(y) : sink;
+                __hip_atomic_fetch_add(dst, (unsigned long long)q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            });
+            __syncthreads();
+            constexpr int kPer = kCoarseBins / kThreads;
+            unsigned long long local = 0, total;
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) local += sh.hist[tid * kPer + i];
+            const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
+            need = (double)top_p * (double)total;
+            if (!((double)excl >= need) && (double)(excl + local) >= need) {
+                unsigned long long acc = excl;
+                for (int i = 0; i < kPer; ++i) {
+                    const unsigned long long h = sh.hist[tid * kPer + i];
+                    if ((double)(acc + h) >= need) {
+                        sh.pick = (uint32_t)(tid * kPer + i);
+                        sh.ckey[kCandCap - 2] = (uint32_t)acc;
+                        sh.ckey[kCandCap - 1] = (uint32_t)(acc >> 32);
+                        break;
+                    }
+                    acc += h;
+                }
+            }
+            __syncthreads();
+            before = (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
+            const int pick_bin = (int)(sh.pick < (uint32_t)kCoarseBins ? sh.pick : (uint32_t)(kCoarseBins - 1));
+            __syncthreads();
+            // the logits of that bin (the bin as a function of the logit is the resident kernel's)
+            sweep([&](uint32_t key, float x) __attribute__((always_inline)) {
+                if (coarse_bin(fmaf(x, k, nr)) == pick_bin) {
+                    const unsigned long long q = mass_q(x, k, nr);
+                    if (q) {
+                        const uint32_t i = atomicAdd(&sh.ncand, 1u);
+                        if (i < (uint32_t)kCandCap) {
+                            sh.ckey[i] = key;
+                            sh.cq[i] = (uint32_t)q;
+                        }
+                    }
+                }
+            });
+            __syncthreads();
+            ncand = sh.ncand;
+            if (ncand > (uint32_t)kCandCap) fall = true;
+        }
+        if (!fall) {
+            for (uint32_t c = tid; c < ncand; c += kThreads) {
+                const uint32_t my = sh.ckey[c];
+                if (sh.cq[c] == 0) continue;
+                unsigned long long above = before, group = 0;
+                for (uint32_t j = 0; j < ncand; ++j) {
+                    const uint32_t o = sh.ckey[j];
+                    const unsigned long long q = sh.cq[j];
+                    above += o > my ? q : 0ull;
+                    group += o == my ? q : 0ull;
+                }
+                if (!((double)above >= need) && (double)(above + group) >= need) sh.pick = my;
+            }
+            __syncthreads();
+            const uint32_t pkey = sh.pick;
+            if (pkey > thr_key) thr_key = pkey;
+        }
+    }
+
+    if (fall) {
+        __syncthreads();
+        thr_key = radix_threshold<DT>(sc.radix, row, V, temp, top_k, top_p);
+    }
+    if (tid == 0) thr_out[r] = K::from_key(thr_key);
+}
+
 }  // namespace
 
 template <int DT>
@@ -1055,7 +1290,27 @@ as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_
     const bool resident = ctx->thr_path != 1 && (has_k || has_p) && ctx->V <= 32768 &&
                           reinterpret_cast<uintptr_t>(logits) % 16 == 0 && (ld * esz) % 16 == 0 &&
                           (!has_k || top_k <= kThreads / 2);
-    if (resident) {
+    const bool streamed = !resident && ctx->thr_path != 1 && (has_k || has_p) &&
+                          reinterpret_cast<uintptr_t>(logits) % 16 == 0 && (ld * esz) % 16 == 0 &&
+                          (!has_k || top_k <= kThreads / 2);
+    if (streamed) {
+        const dim3 grid((unsigned)rows), block(kThreads);
+#define AS_STREAM_LAUNCH(DT_)                                                                                    \
+    do {                                                                                                         \
+        if (has_k && has_p)                                                                                      \
+            launch(ctx, kKernelThreshold, threshold_stream_kernel<DT_, true, true>, grid, block, 0, logits, ld,  \
+                   ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);                                   \
+        else if (has_k)                                                                                          \
+            launch(ctx, kKernelThreshold, threshold_stream_kernel<DT_, true, false>, grid, block, 0, logits, ld, \
+                   ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);                                   \
+        else                                                                                                     \
+            launch(ctx, kKernelThreshold, threshold_stream_kernel<DT_, false, true>, grid, block, 0, logits, ld, \
+                   ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);                                   \
+    } while (0)
+        if (ctx->dtype == AS_BF16) AS_STREAM_LAUNCH(AS_BF16);
+        else AS_STREAM_LAUNCH(AS_F32);
+#undef AS_STREAM_LAUNCH
+    } else if (resident) {
         if (ctx->dtype == AS_BF16)
             launch_resident<AS_BF16>(ctx, logits, rows, ld, finished_in, row_ids, temp, top_k, top_p, thr_out, has_k,
                                      has_p);
