@@ -18,9 +18,10 @@
 // so it is the general path only.  Rows of up to 32768 logits that can be read in
 // 16-byte pieces take the resident path further down: the row is loaded once into
 // registers, a coarse histogram with evenly filled bins finds the neighbourhood of
-// the answer, and the few logits in that neighbourhood are ranked exactly.  Both
-// paths use the same keys and the same fixed-point masses, so they return the
-// same threshold.
+// the answer, and the few logits in that neighbourhood are ranked exactly.  Longer
+// rows take the same method with passes over memory instead (the streamed path at
+// the end).  All paths use the same keys and the same fixed-point masses, so they
+// return the same threshold.
 #include <type_traits>
 
 #include "as_common.hpp"
