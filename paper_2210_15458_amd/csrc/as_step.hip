@@ -185,8 +185,17 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
     const int64_t src = a.row_ids ? (int64_t)a.row_ids[r] : r;
     const unsigned char *rowb =
         reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.logits) + src * a.ld);
-    const int32_t nvec = (a.V + EPV - 1) / EPV;   // the last vector may be partial: rem of its elements are the row's
-    const int32_t rem = PARTIAL ? a.V % EPV : 0;
+    // PARTIAL: the row is read as the whole 16-byte vectors it touches; `shift` elements of the first one lie
+    // before the row and (with `rem` != 0) the last one holds only `rem` elements of it
+    int32_t shift = 0;
+    if constexpr (PARTIAL) {
+        const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(rowb) & 15u);
+        rowb -= mis;
+        shift = (int32_t)(mis / sizeof(T));
+    }
+    const int32_t vlen = a.V + shift;              // the row's end, counted from the first vector's first element
+    const int32_t nvec = (vlen + EPV - 1) / EPV;
+    const int32_t rem = PARTIAL ? vlen % EPV : 0;
     const float k = a.k;
     float thr = 0.f;
     if constexpr (HAS_THR) thr = a.thr[r];
@@ -245,15 +254,17 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
 #pragma unroll
                     for (int i = 0; i < EPV; ++i) x[jj][i] = (x[jj][i] >= thr) ? x[jj][i] : -__builtin_inff();
                 }
-                if constexpr (RAGGED && PARTIAL) {
-                    if (rem != 0) {
-                        // what follows the row in its partial last vector is no logit; lanes past the row's end
-                        // may have re-read that vector too
-                        uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
-                        off = off < off_last ? off : off_last;
-                        const bool part = off == tail_off;
+                if constexpr (PARTIAL) {
+                    // What lies before the row in its first vector and after it in its last one is no logit.
+                    // A lane past the row's end has re-read one of its earlier vectors, or the share's first.
+                    uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                    if constexpr (RAGGED) off = off < off_last ? off : off_last;
+                    const bool head = shift != 0 && v0 == 0 && off == 0u;
+                    const bool tail = RAGGED && rem != 0 && off == tail_off;
+                    if (shift != 0 || rem != 0) {
 #pragma unroll
-                        for (int i = 0; i < EPV; ++i) x[jj][i] = (part && i >= rem) ? -__builtin_inff() : x[jj][i];
+                        for (int i = 0; i < EPV; ++i)
+                            x[jj][i] = ((head && i < shift) || (tail && i >= rem)) ? -__builtin_inff() : x[jj][i];
                     }
                 }
                 m[jj] = vec_max<EPV>(x[jj]);
@@ -456,12 +467,15 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
     float x[EPV];
     unpack<DT>(hv, x);
     double ed[EPV];
-    const bool partial = PARTIAL && rem != 0 && (int64_t)ts * kTile + (int64_t)wave * kShare + (int64_t)cj * 64 + lane == nvec - 1;
+    const int64_t vec_no = (int64_t)ts * kTile + (int64_t)wave * kShare + (int64_t)cj * 64 + lane;
+    const bool last_partial = PARTIAL && rem != 0 && vec_no == nvec - 1;
+    const bool first_partial = PARTIAL && shift != 0 && vec_no == 0;
 #pragma unroll
     for (int i = 0; i < EPV; ++i) {
         float e = fast_exp2(fmaf(x[i], k, -rh));
         if constexpr (HAS_THR) e = (x[i] >= thr) ? e : 0.f;
-        if (partial && i >= rem) e = 0.f;
+        if (last_partial && i >= rem) e = 0.f;
+        if (first_partial && i < shift) e = 0.f;
         ed[i] = (double)ldexpf(e, shf);
     }
     double acc = incl2 - lv;
@@ -475,7 +489,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
     }
     if (ih < 0) { ih = ilast; before = before_last; ev = ev_last; }
 
-    int64_t tok64 = ((int64_t)ts * kTile + (int64_t)wave * kShare + (int64_t)cj * 64 + lane) * EPV + ih;
+    int64_t tok64 = vec_no * EPV + ih - shift;
     if (tok64 > a.V - 1) tok64 = a.V - 1;
     if (tok64 < 0) tok64 = 0;
     RowOut o;
@@ -517,12 +531,15 @@ template <int DT, int NW, int ITERS, int OCC, bool HAS_THR>
 as_status launch_shape(as_ctx *ctx, const StepArgs &a)
 {
     constexpr int EPV = Elem<DT>::kPerVec;
-    const int64_t nvec = ((int64_t)a.V + EPV - 1) / EPV;
+    const bool whole = a.V % EPV == 0 && reinterpret_cast<uintptr_t>(a.logits) % 16 == 0 &&
+                       (a.ld * (int64_t)sizeof(typename Elem<DT>::T)) % 16 == 0;
+    // a row that does not start on 16 bytes can touch one vector more
+    const int64_t nvec = ((int64_t)a.V + (whole ? 0 : EPV - 1) + EPV - 1) / EPV;
     const int64_t tile = (int64_t)NW * ITERS * 64;
     const int ntiles = (int)((nvec + tile - 1) / tile);
     const size_t lds = ((size_t)NW * ITERS * 64 + (size_t)ntiles * NW * 2) * sizeof(float);
     if (lds > 60 * 1024) return fail(ctx, AS_ERR_UNSUPPORTED, "vocabulary too large for the share table");
-    if (a.V % EPV != 0)
+    if (!whole)
         launch(ctx, kKernelStep, step_kernel<DT, NW, ITERS, OCC, HAS_THR, true>, dim3((unsigned)a.rows), dim3(NW * 64),
                lds, a, ntiles);
     else
@@ -549,8 +566,8 @@ template <int DT>
 as_status launch_dt(as_ctx *ctx, const StepArgs &a)
 {
     const size_t esz = (DT == AS_BF16) ? 2 : 4;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.logits) % 16 == 0) && ((a.ld * esz) % 16 == 0);
-    if (aligned && ctx->step_shape != 9)
+    // the fast kernel reads whole 16-byte vectors; all it needs of the rows is that they start on an element
+    if (reinterpret_cast<uintptr_t>(a.logits) % esz == 0 && ctx->step_shape != 9)
         return a.thr ? launch_fast<DT, true>(ctx, a) : launch_fast<DT, false>(ctx, a);
     if (a.thr) launch(ctx, kKernelStep, step_generic_kernel<DT, true>, dim3((unsigned)a.rows), dim3(256), 0, a);
     else launch(ctx, kKernelStep, step_generic_kernel<DT, false>, dim3((unsigned)a.rows), dim3(256), 0, a);

@@ -167,6 +167,14 @@ def test_step_shape_sweep(V, dtype):
                    sigma=float(rng.choice([0.5, 3.0, 8.0])), seed=int(rng.integers(1, 1 << 30)))
 
 
+def test_step_three_pass_kernel(monkeypatch):
+    # the plain three-pass kernel, which no shape needs any more, forced by its knob
+    monkeypatch.setenv("AS_STEP_SHAPE", "9")
+    _check(1001, 24, "bf16", seed=41)
+    _check(4097, 12, "f32", temp=0.7, top_k=40, seed=42)
+    _check(32128, 8, "bf16", top_p=0.9, seed=43)
+
+
 def test_step_truncation_multi_tile():
     _check(256000, 6, "bf16", top_k=40, seed=33)
     _check(256000, 6, "bf16", top_p=0.9, seed=34)
