@@ -992,8 +992,8 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
 
 // ------------------------------------------------------------ streamed path
 //
-// Rows too long for the registers (more than 32768 logits), readable in 16-byte pieces, k at most half the
-// thread count: the method of the resident kernel with every visit of the row a pass over memory, four pieces
+// Rows too long for the registers (more than 32768 logits) or not laid out in whole 16-byte pieces, k at most
+// half the thread count: the method of the resident kernel with every visit of the row a pass over memory, four pieces
 // per thread in flight.  Top-k takes two passes (thread maxima, then the logits at or above the bound they
 // give), the nucleus alone three (maximum, mass per coarse bin, the logits of the bin where the nucleus
 // closes); the nucleus after top-k works on the candidate table.  Same keys, same fixed-point masses, same
@@ -1016,7 +1016,11 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
     if (finished_in != nullptr && finished_in[r] != 0) return;
     const int64_t src = row_ids ? (int64_t)row_ids[r] : r;
     const T *row = reinterpret_cast<const T *>(logits) + src * ld;
-    const int32_t npieces = (V + EPP - 1) / EPP;
+    // the row as the whole 16-byte pieces it touches: `shift` elements of the first one lie before it
+    const int32_t shift = (int32_t)((reinterpret_cast<uintptr_t>(row) & 15u) / sizeof(T));
+    const u32x4 *const pieces = reinterpret_cast<const u32x4 *>(row - shift);
+    const int32_t vend = V + shift;
+    const int32_t npieces = (vend + EPP - 1) / EPP;
 
     // f(key, value) for every logit of the row (value: the stored logit widened to fp32), each once
     auto sweep = [&](auto f) __attribute__((always_inline)) {
@@ -1025,21 +1029,23 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int32_t piece = base + u * kThreads;
-                w[u] = piece < npieces ? reinterpret_cast<const u32x4 *>(row)[piece] : u32x4{0, 0, 0, 0};
+                w[u] = piece < npieces ? pieces[piece] : u32x4{0, 0, 0, 0};
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int32_t piece = base + u * kThreads;
                 if (piece >= npieces) break;
-                const int32_t live = V - piece * EPP;              // logits of the row in this piece (>= EPP: all)
+                // elements [first, live) of this piece are the row's (all of them except at the row's two ends)
+                const int32_t first = piece == 0 ? shift : 0, live = vend - piece * EPP;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t d = w[u][i];
                     if constexpr (kHalf) {
-                        if (2 * i < live) f(K::key((T)(d & 0xffffu)), __builtin_bit_cast(float, d << 16));
-                        if (2 * i + 1 < live) f(K::key((T)(d >> 16)), __builtin_bit_cast(float, d & 0xffff0000u));
+                        if (2 * i >= first && 2 * i < live) f(K::key((T)(d & 0xffffu)), __builtin_bit_cast(float, d << 16));
+                        if (2 * i + 1 >= first && 2 * i + 1 < live)
+                            f(K::key((T)(d >> 16)), __builtin_bit_cast(float, d & 0xffff0000u));
                     } else {
-                        if (i < live) f(K::key(__builtin_bit_cast(float, d)), __builtin_bit_cast(float, d));
+                        if (i >= first && i < live) f(K::key(__builtin_bit_cast(float, d)), __builtin_bit_cast(float, d));
                     }
                 }
             }
@@ -1292,8 +1298,7 @@ as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_
                           reinterpret_cast<uintptr_t>(logits) % 16 == 0 && (ld * esz) % 16 == 0 &&
                           (!has_k || top_k <= kThreads / 2);
     const bool streamed = !resident && ctx->thr_path != 1 && (has_k || has_p) &&
-                          reinterpret_cast<uintptr_t>(logits) % 16 == 0 && (ld * esz) % 16 == 0 &&
-                          (!has_k || top_k <= kThreads / 2);
+                          reinterpret_cast<uintptr_t>(logits) % esz == 0 && (!has_k || top_k <= kThreads / 2);
     if (streamed) {
         const dim3 grid((unsigned)rows), block(kThreads);
 #define AS_STREAM_LAUNCH(DT_)                                                                                    \
