@@ -16,51 +16,44 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__device__ __forceinline__ float widen(float x) { return x; }
-__device__ __forceinline__ float widen(uint16_t h) { return __builtin_bit_cast(float, (uint32_t)h << 16); }
 
-// g(v0, x[0..n)) over the row's logits in runs of up to 8 consecutive ones starting at v0, each logit exactly
-// once per thread block.  Rows that can be read in 16-byte pieces are (VEC): four pieces in flight per
-// thread; the others go element by element.
-template <class T, bool VEC, class G>
+// g(v0, x, first, n) over the row's logits in runs: elements first..n-1 of x are logits v0+first..v0+n-1 of the
+// row, each logit of the row exactly once per thread block.  The row is read as the whole 16-byte pieces it
+// touches, four in flight per thread; only the pieces at the row's two ends have first > 0 or n < 8 (4).
+template <class T, class G>
 __device__ __forceinline__ void for_row(const T *row, int32_t V, G g)
 {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     constexpr int EPP = 16 / (int)sizeof(T);
-    if constexpr (VEC) {
-        const int32_t npieces = (V + EPP - 1) / EPP;
-        for (int32_t base = threadIdx.x; base < npieces; base += 4 * kThreads) {
-            u32x4 w[4];
+    const int32_t shift = (int32_t)((reinterpret_cast<uintptr_t>(row) & 15u) / sizeof(T));
+    const u32x4 *const pieces = reinterpret_cast<const u32x4 *>(row - shift);
+    const int32_t vend = V + shift;
+    const int32_t npieces = (vend + EPP - 1) / EPP;
+    for (int32_t base = threadIdx.x; base < npieces; base += 4 * kThreads) {
+        u32x4 w[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int32_t piece = base + u * kThreads;
-                w[u] = piece < npieces ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + piece)
-                                       : u32x4{0, 0, 0, 0};
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int32_t piece = base + u * kThreads;
-                if (piece >= npieces) break;
-                const int32_t v0 = piece * EPP;
-                float x[EPP];
-#pragma unroll
-                for (int e = 0; e < EPP; ++e) {
-                    if constexpr (sizeof(T) == 2) {
-                        const uint32_t word = w[u][e >> 1];
-                        x[e] = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
-                    } else {
-                        const uint32_t word = w[u][e];
-                        x[e] = __builtin_bit_cast(float, word);
-                    }
-                }
-                const int n = V - v0 < EPP ? V - v0 : EPP;
-                g(v0, x, n, std::integral_constant<int, EPP>{});
-            }
+        for (int u = 0; u < 4; ++u) {
+            const int32_t piece = base + u * kThreads;
+            w[u] = piece < npieces ? __builtin_nontemporal_load(pieces + piece) : u32x4{0, 0, 0, 0};
         }
-    } else {
-        for (int32_t v = threadIdx.x; v < V; v += kThreads) {
-            float x[1] = {widen(row[v])};
-            g(v, x, 1, std::integral_constant<int, 1>{});
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int32_t piece = base + u * kThreads;
+            if (piece >= npieces) break;
+            float x[EPP];
+#pragma unroll
+            for (int e = 0; e < EPP; ++e) {
+                if constexpr (sizeof(T) == 2) {
+                    const uint32_t word = w[u][e >> 1];
+                    x[e] = __builtin_bit_cast(float, (e & 1) ? (word & 0xffff0000u) : (word << 16));
+                } else {
+                    const uint32_t word = w[u][e];
+                    x[e] = __builtin_bit_cast(float, word);
+                }
+            }
+            const int32_t left = vend - piece * EPP;
+            g(piece * EPP - shift, x, piece == 0 ? shift : 0, left < EPP ? left : EPP,
+              std::integral_constant<int, EPP>{});
         }
     }
 }
@@ -87,9 +80,9 @@ __device__ __forceinline__ void block_sum3(double &a, double &b, double &c, doub
     }
 }
 
-// VEC: rows are read in 16-byte pieces (else element by element).  One pass over memory: every thread keeps an
-// integer reference that follows the largest logit it has seen (see below).
-template <class T, bool VEC>
+// One pass over memory: every thread keeps an integer reference that follows the largest logit it has seen (see
+// below).
+template <class T>
 __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
 {
     __shared__ double scratch[3 * (kThreads / 64)];
@@ -109,19 +102,19 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
     const float thr = a.thr ? a.thr[r] : -__builtin_inff();
     const float k = a.k;
 
-    auto each_run = [&](auto g) __attribute__((always_inline)) { for_row<T, VEC>(row, a.V, g); };
+    auto each_run = [&](auto g) __attribute__((always_inline)) { for_row<T>(row, a.V, g); };
 
-    // a run as the sums see it: what is cut off by the threshold or lies past the row's end counts as -inf
+    // a run as the sums see it: what is cut off by the threshold or lies outside the row counts as -inf
     // (weight exactly 0); whole runs of an untruncated row, nearly all of them, pass through untouched
     const bool cut = a.thr != nullptr;
-    auto kept = [&](const float *x, int n, auto cap, float *y) __attribute__((always_inline)) {
+    auto kept = [&](const float *x, int first, int n, auto cap, float *y) __attribute__((always_inline)) {
         constexpr int E = decltype(cap)::value;
-        if (!cut && n == E) {
+        if (!cut && first == 0 && n == E) {
 #pragma unroll
             for (int e = 0; e < E; ++e) y[e] = x[e];
         } else {
 #pragma unroll
-            for (int e = 0; e < E; ++e) y[e] = (e < n && x[e] >= thr) ? x[e] : -__builtin_inff();
+            for (int e = 0; e < E; ++e) y[e] = (e >= first && e < n && x[e] >= thr) ? x[e] : -__builtin_inff();
         }
     };
 
@@ -163,10 +156,10 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
             at = ldexp(at, down);
             ref = to;
         };
-        each_run([&](int32_t v0, const float *x, int n, auto cap) __attribute__((always_inline)) {
+        each_run([&](int32_t v0, const float *x, int first, int n, auto cap) __attribute__((always_inline)) {
             constexpr int E = decltype(cap)::value;
             float y[E];
-            kept(x, n, cap, y);
+            kept(x, first, n, cap, y);
             float pm = y[0];
 #pragma unroll
             for (int e = 1; e < E; ++e) pm = fmaxf(pm, y[e]);
@@ -211,16 +204,9 @@ __global__ void interval_init_kernel(int32_t B, int32_t N, const int32_t *prompt
 as_status launch_interval(as_ctx *ctx, const IntervalArgs &a)
 {
     if (a.rows == 0) return AS_OK;
-    const size_t esz = a.dtype == AS_BF16 ? 2 : 4;
-    const bool vec = reinterpret_cast<uintptr_t>(a.logits) % 16 == 0 && (a.ld * esz) % 16 == 0;
     const dim3 grid((unsigned)a.rows), block(kThreads);
-    if (a.dtype == AS_BF16) {
-        if (vec) launch(ctx, kKernelInterval, interval_kernel<uint16_t, true>, grid, block, 0, a);
-        else launch(ctx, kKernelInterval, interval_kernel<uint16_t, false>, grid, block, 0, a);
-    } else {
-        if (vec) launch(ctx, kKernelInterval, interval_kernel<float, true>, grid, block, 0, a);
-        else launch(ctx, kKernelInterval, interval_kernel<float, false>, grid, block, 0, a);
-    }
+    if (a.dtype == AS_BF16) launch(ctx, kKernelInterval, interval_kernel<uint16_t>, grid, block, 0, a);
+    else launch(ctx, kKernelInterval, interval_kernel<float>, grid, block, 0, a);
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }

@@ -31,7 +31,7 @@ def _interval_step(stored, tokens, V, temp=1.0, top_k=0, top_p=1.0, finished=Non
 
 
 _MODS = [(1.0, 0, 1.0), (0.7, 0, 1.0), (1.0, 40, 1.0), (1.0, 0, 0.9)]
-# both forms of the kernel (element by element for odd strides, 16-byte pieces otherwise), rows shorter than a
+# rows that start on and off 16 bytes (odd strides), rows shorter than a
 # block's one sweep and rows of many sweeps, every logit modifier on the general shapes, the untruncated ones
 # on three more lengths, one plain case on the large vocabulary
 _INTERVAL_CASES = (
