@@ -111,9 +111,13 @@ as_status as_ctx_profile_samples(as_ctx *ctx, int kernel, float *ms_out,
  * F(v) > c, i.e. c lies in [F(v-1), F(v)); c' = (c - F(v-1)) / (F(v) -
  * F(v-1)).  Arithmetic is fp32 per element with fp64 carries.
  *
- *   logits      DEVICE [rows, ld] row-major, ctx dtype, ld >= V; columns
- *               V..ld-1 are never read.  Rows whose start is 16-byte aligned
- *               take the vector path; others a slower element path.
+ *   logits      DEVICE [rows, ld] row-major, ctx dtype, ld >= V, any stride.
+ *               Columns V..ld-1 are never used.  Memory is read in whole,
+ *               aligned 16-byte pieces, so the bytes that share a 16-byte
+ *               granule with a row's first or last logit may be loaded (and
+ *               discarded); nothing outside those granules is touched.  Rows
+ *               that start on 16 bytes and are a whole number of such pieces
+ *               long (V * element size a multiple of 16) run a little faster.
  *   codes       DEVICE float[rows], each in [0,1)
  *   temp        > 0
  *   top_k       keep the k highest logits and everything tied with the k-th;
