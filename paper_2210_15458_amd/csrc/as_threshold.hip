@@ -994,11 +994,14 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
 //
 // Rows too long for the registers (more than 32768 logits) or not laid out in whole 16-byte pieces, k at most
 // half the thread count: the method of the resident kernel with every visit of the row a pass over memory, four pieces
-// per thread in flight.  Top-k takes two passes (thread maxima, then the logits at or above the bound they
-// give), the nucleus alone three (maximum, mass per coarse bin, the logits of the bin where the nucleus
+// per thread in flight.  Top-k with k up to 128 takes two passes (thread maxima, then the logits at or above
+// the bound they give), any larger k three (maximum, count per coarse bin, the logits of the bin that holds
+// the k-th), the nucleus alone three (maximum, mass per coarse bin, the logits of the bin where the nucleus
 // closes); the nucleus after top-k works on the candidate table.  Same keys, same fixed-point masses, same
 // fall-back as the other two kernels, so the same threshold.
-template <int DT, bool HAS_K, bool HAS_P>
+// KMODE 0: no top-k; 1: bound from the thread maxima (k at most half the thread count); 2: any k, by counts per
+// coarse bin, the way the nucleus goes by mass per coarse bin.
+template <int DT, int KMODE, bool HAS_P>
 __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *logits, int64_t ld, int32_t V,
                                                                     const uint8_t *finished_in,
                                                                     const int32_t *row_ids, float temp,
@@ -1057,6 +1060,7 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
     bool fall = false;
     uint32_t ncand = 0;
 
+    constexpr bool HAS_K = KMODE == 1;
     if (HAS_K) {
         // the k-th largest of the thread maxima bounds the k-th largest logit from below
         uint32_t tmax = 0;
@@ -1112,12 +1116,115 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
         __syncthreads();
     }
 
-    if (HAS_P && !fall) {
-        const float k = 1.44269504088896340736f / temp;
-        double need;
-        unsigned long long before = 0;
+    const float k = 1.44269504088896340736f / temp;
+
+    // The row's integer reference (for the bins and the masses), by one pass.
+    auto row_reference = [&]() __attribute__((always_inline)) {
+        float m = -__builtin_inff();
+        sweep([&](uint32_t, float x) __attribute__((always_inline)) { m = fmaxf(m, x); });
+        m = wave_max(m);
+        float *fred = reinterpret_cast<float *>(sh.ckey);
+        __syncthreads();
+        if ((tid & 63) == 0) fred[tid >> 6] = m;
+        __syncthreads();
+        m = fred[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
+        __syncthreads();
+        return -fmaxf(ceilf(m * k), -100000.f);
+    };
+
+    // One selection over the whole row by coarse bins.  weigh(key, x) is a logit's integer weight: 1 to count
+    // it, its fixed-point mass for the nucleus, 0 to leave it out; goal(total) is what the running weight,
+    // from the largest logit down, has to reach.  Two passes: weight per bin, then the logits of the bin in
+    // which the goal is reached, ranked exactly; the group of equal logits that reaches it stays whole and
+    // its key becomes the threshold.
+    auto select = [&](float nr, auto weigh, auto goal) __attribute__((always_inline)) {
+        for (int b = tid; b < kCoarseBins; b += kThreads) sh.hist[b] = 0;
+        if (tid == 0) sh.ncand = 0;
+        __syncthreads();
+        typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+        lds_u64 *const bins = (lds_u64 *)sh.hist;
+        lds_u64 *const sink = (lds_u64 *)sh.mcount + (tid & 63);      // where a weight of zero is "added"
+        sweep([&](uint32_t key, float x) __attribute__((always_inline)) {
+            const unsigned long long q = weigh(key, x);
+            lds_u64 *const dst = q ? bins + coarse_bin_nonpositive(fmaf(x, k, nr)) : sink;
+            __hip_atomic_fetch_add(dst, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        });
+        __syncthreads();
+        constexpr int kPer = kCoarseBins / kThreads;
+        unsigned long long local = 0, total;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) local += sh.hist[tid * kPer + i];
+        const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
+        const double need = goal(total);
+        if (!((double)excl >= need) && (double)(excl + local) >= need) {
+            unsigned long long acc = excl;
+            for (int i = 0; i < kPer; ++i) {
+                const unsigned long long h = sh.hist[tid * kPer + i];
+                if ((double)(acc + h) >= need) {
+                    sh.pick = (uint32_t)(tid * kPer + i);
+                    sh.ckey[kCandCap - 2] = (uint32_t)acc;
+                    sh.ckey[kCandCap - 1] = (uint32_t)(acc >> 32);
+                    break;
+                }
+                acc += h;
+            }
+        }
+        __syncthreads();
+        const unsigned long long before =
+            (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
+        const int pick_bin = (int)(sh.pick < (uint32_t)kCoarseBins ? sh.pick : (uint32_t)(kCoarseBins - 1));
+        __syncthreads();
+        sweep([&](uint32_t key, float x) __attribute__((always_inline)) {
+            if (coarse_bin(fmaf(x, k, nr)) == pick_bin) {
+                const unsigned long long q = weigh(key, x);
+                if (q) {
+                    const uint32_t i = atomicAdd(&sh.ncand, 1u);
+                    if (i < (uint32_t)kCandCap) {
+                        sh.ckey[i] = key;
+                        sh.cq[i] = (uint32_t)q;
+                    }
+                }
+            }
+        });
+        __syncthreads();
+        ncand = sh.ncand;
+        if (ncand > (uint32_t)kCandCap) {
+            fall = true;
+            return;
+        }
+        for (uint32_t c = tid; c < ncand; c += kThreads) {
+            const uint32_t my = sh.ckey[c];
+            if (sh.cq[c] == 0) continue;
+            unsigned long long above = before, group = 0;
+            for (uint32_t j = 0; j < ncand; ++j) {
+                const uint32_t o = sh.ckey[j];
+                const unsigned long long q = sh.cq[j];
+                above += o > my ? q : 0ull;
+                group += o == my ? q : 0ull;
+            }
+            if (!((double)above >= need) && (double)(above + group) >= need) sh.pick = my;
+        }
+        __syncthreads();
+        const uint32_t pkey = sh.pick;
+        if (pkey > thr_key) thr_key = pkey;
+        __syncthreads();
+    };
+
+    if (KMODE == 2) {
+        // top-k for any k: count the logits per coarse bin from the top until k are reached
+        const float nr = row_reference();
+        select(nr, [](uint32_t, float) { return 1ull; }, [&](unsigned long long) { return (double)top_k; });
+        if (HAS_P && !fall) {
+            const uint32_t floor_key = thr_key;
+            select(nr, [&](uint32_t key, float x) { return key >= floor_key ? mass_q(x, k, nr) : 0ull; },
+                   [&](unsigned long long total) { return (double)top_p * (double)total; });
+        }
+    } else if (HAS_P && !fall) {
         if (HAS_K) {
             // every survivor of top-k is in the candidate table
+            double need;
             float m = -__builtin_inff();
             for (uint32_t c = tid; c < ncand; c += kThreads)
                 if (sh.ckey[c] >= thr_key) m = fmaxf(m, K::from_key(sh.ckey[c]));
@@ -1139,76 +1246,10 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
             block_excl_scan(local, sh.wave_tot, total);
             need = (double)top_p * (double)total;
             __syncthreads();
-        } else {
-            float m = -__builtin_inff();
-            sweep([&](uint32_t, float x) __attribute__((always_inline)) { m = fmaxf(m, x); });
-            m = wave_max(m);
-            float *fred = reinterpret_cast<float *>(sh.ckey);
-            if ((tid & 63) == 0) fred[tid >> 6] = m;
-            for (int b = tid; b < kCoarseBins; b += kThreads) sh.hist[b] = 0;
-            if (tid == 0) sh.ncand = 0;
-            __syncthreads();
-            m = fred[0];
-#pragma unroll
-            for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
-            const float nr = -fmaxf(ceilf(m * k), -100000.f);
-            __syncthreads();
-            typedef __attribute__((address_space(3))) unsigned long long lds_u64;
-            lds_u64 *const bins = (lds_u64 *)sh.hist;
-            lds_u64 *const sink = (lds_u64 *)sh.mcount + (tid & 63);
-            sweep([&](uint32_t, float x) __attribute__((always_inline)) {
-                const float y = fmaf(x, k, nr);
-                const float e = __builtin_amdgcn_exp2f(y);
-                const uint32_t q = (uint32_t)(e * 2147483648.f + 0.5f);
-                lds_u64 *const dst = q ? bins + coarse_bin_nonpositive(y) : sink;
-                __hip_atomic_fetch_add(dst, (unsigned long long)q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            });
-            __syncthreads();
-            constexpr int kPer = kCoarseBins / kThreads;
-            unsigned long long local = 0, total;
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) local += sh.hist[tid * kPer + i];
-            const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
-            need = (double)top_p * (double)total;
-            if (!((double)excl >= need) && (double)(excl + local) >= need) {
-                unsigned long long acc = excl;
-                for (int i = 0; i < kPer; ++i) {
-                    const unsigned long long h = sh.hist[tid * kPer + i];
-                    if ((double)(acc + h) >= need) {
-                        sh.pick = (uint32_t)(tid * kPer + i);
-                        sh.ckey[kCandCap - 2] = (uint32_t)acc;
-                        sh.ckey[kCandCap - 1] = (uint32_t)(acc >> 32);
-                        break;
-                    }
-                    acc += h;
-                }
-            }
-            __syncthreads();
-            before = (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
-            const int pick_bin = (int)(sh.pick < (uint32_t)kCoarseBins ? sh.pick : (uint32_t)(kCoarseBins - 1));
-            __syncthreads();
-            // the logits of that bin (the bin as a function of the logit is the resident kernel's)
-            sweep([&](uint32_t key, float x) __attribute__((always_inline)) {
-                if (coarse_bin(fmaf(x, k, nr)) == pick_bin) {
-                    const unsigned long long q = mass_q(x, k, nr);
-                    if (q) {
-                        const uint32_t i = atomicAdd(&sh.ncand, 1u);
-                        if (i < (uint32_t)kCandCap) {
-                            sh.ckey[i] = key;
-                            sh.cq[i] = (uint32_t)q;
-                        }
-                    }
-                }
-            });
-            __syncthreads();
-            ncand = sh.ncand;
-            if (ncand > (uint32_t)kCandCap) fall = true;
-        }
-        if (!fall) {
             for (uint32_t c = tid; c < ncand; c += kThreads) {
                 const uint32_t my = sh.ckey[c];
                 if (sh.cq[c] == 0) continue;
-                unsigned long long above = before, group = 0;
+                unsigned long long above = 0, group = 0;
                 for (uint32_t j = 0; j < ncand; ++j) {
                     const uint32_t o = sh.ckey[j];
                     const unsigned long long q = sh.cq[j];
@@ -1220,6 +1261,10 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
             __syncthreads();
             const uint32_t pkey = sh.pick;
             if (pkey > thr_key) thr_key = pkey;
+        } else {
+            const float nr = row_reference();
+            select(nr, [&](uint32_t, float x) { return mass_q(x, k, nr); },
+                   [&](unsigned long long total) { return (double)top_p * (double)total; });
         }
     }
 
@@ -1297,24 +1342,26 @@ as_status launch_threshold(as_ctx *ctx, const void *logits, int64_t rows, int64_
     const bool resident = ctx->thr_path != 1 && (has_k || has_p) && ctx->V <= 32768 &&
                           reinterpret_cast<uintptr_t>(logits) % 16 == 0 && (ld * esz) % 16 == 0 &&
                           (!has_k || top_k <= kThreads / 2);
+    // what the resident kernel does not take goes to the streamed one (any row length and stride, any k)
     const bool streamed = !resident && ctx->thr_path != 1 && (has_k || has_p) &&
-                          reinterpret_cast<uintptr_t>(logits) % esz == 0 && (!has_k || top_k <= kThreads / 2);
+                          reinterpret_cast<uintptr_t>(logits) % esz == 0;
     if (streamed) {
         const dim3 grid((unsigned)rows), block(kThreads);
+        const int kmode = !has_k ? 0 : top_k <= kThreads / 2 ? 1 : 2;
+#define AS_STREAM_LAUNCH1(DT_, KM_, HP_)                                                                        \
+    launch(ctx, kKernelThreshold, threshold_stream_kernel<DT_, KM_, HP_>, grid, block, 0, logits, ld, ctx->V,   \
+           finished_in, row_ids, temp, top_k, top_p, thr_out)
 #define AS_STREAM_LAUNCH(DT_)                                                                                    \
     do {                                                                                                         \
-        if (has_k && has_p)                                                                                      \
-            launch(ctx, kKernelThreshold, threshold_stream_kernel<DT_, true, true>, grid, block, 0, logits, ld,  \
-                   ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);                                   \
-        else if (has_k)                                                                                          \
-            launch(ctx, kKernelThreshold, threshold_stream_kernel<DT_, true, false>, grid, block, 0, logits, ld, \
-                   ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);                                   \
-        else                                                                                                     \
-            launch(ctx, kKernelThreshold, threshold_stream_kernel<DT_, false, true>, grid, block, 0, logits, ld, \
-                   ctx->V, finished_in, row_ids, temp, top_k, top_p, thr_out);                                   \
+        if (kmode == 0) AS_STREAM_LAUNCH1(DT_, 0, true);                                                         \
+        else if (kmode == 1 && has_p) AS_STREAM_LAUNCH1(DT_, 1, true);                                           \
+        else if (kmode == 1) AS_STREAM_LAUNCH1(DT_, 1, false);                                                   \
+        else if (has_p) AS_STREAM_LAUNCH1(DT_, 2, true);                                                         \
+        else AS_STREAM_LAUNCH1(DT_, 2, false);                                                                   \
     } while (0)
         if (ctx->dtype == AS_BF16) AS_STREAM_LAUNCH(AS_BF16);
         else AS_STREAM_LAUNCH(AS_F32);
+#undef AS_STREAM_LAUNCH1
 #undef AS_STREAM_LAUNCH
     } else if (resident) {
         if (ctx->dtype == AS_BF16)

@@ -108,13 +108,16 @@ def test_step_is_deterministic_and_in_place():
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("top_k,top_p,temp", [(40, 1.0, 1.0), (0, 0.9, 1.0), (1, 1.0, 1.0), (5, 0.5, 0.7),
-                                              (1000, 0.95, 1.3), (0, 0.3, 0.8)])
+                                              (1000, 0.95, 1.3), (0, 0.3, 0.8),
+                                              # k beyond what the thread maxima can bound: by counts per bin
+                                              (129, 0.9, 1.0), (200, 1.0, 1.0), (5000, 1.0, 0.7)])
 def test_step_truncation(dtype, top_k, top_p, temp):
     _check(32128, 64, dtype, temp=temp, top_k=top_k, top_p=top_p, seed=31)
     _check(1001, 40, dtype, temp=temp, top_k=min(top_k, 900), top_p=top_p, seed=32)
     # rows that take the register-resident kernels and end inside a 16-byte piece (the padding holds +1e30)
-    _check(1001, 40, dtype, temp=temp, top_k=top_k, top_p=top_p, ld=1008, seed=37)
-    _check(4099, 24, dtype, temp=temp, top_k=top_k, top_p=top_p, ld=4104, seed=38)
+    _check(1001, 40, dtype, temp=temp, top_k=min(top_k, 900), top_p=top_p, ld=1008, seed=37)
+    _check(4099, 24, dtype, temp=temp, top_k=min(top_k, 4000), top_p=top_p, ld=4104, seed=38)
+    _check(50257, 8, dtype, temp=temp, top_k=top_k, top_p=top_p, seed=39)
 
 
 @pytest.mark.parametrize("top_k,top_p", [(40, 1.0), (0, 0.9), (5, 0.5)])
