@@ -313,6 +313,151 @@ __device__ __forceinline__ int coarse_bin_nonpositive(float y)
     return (int)(__builtin_bit_cast(uint32_t, t) - 0x4B000000u);
 }
 
+// ---- stages that work on the block's LDS tables only; every thread of the block calls them
+
+// Top-k with k at most half the thread count, first half: each thread brings the largest key it holds; the k-th
+// largest of those bounds the k-th largest logit from below.  Returns a key at or below it: the lowest thread
+// maximum among the bins (256, even over the range of the maxima, from the top) that hold the first k of them.
+// Also empties the candidate table.
+__device__ __forceinline__ uint32_t bound_from_thread_maxima(Resident &sh, uint32_t tmax, int32_t top_k)
+{
+    const int tid = threadIdx.x;
+    sh.mcount[tid] = 0;
+    if (tid == 0) sh.ncand = 0;
+    uint32_t hi = wave_reduce_umax(tmax), lo = wave_reduce_umin(tmax);
+    uint32_t *red = reinterpret_cast<uint32_t *>(sh.hist);
+    if ((tid & 63) == 0) { red[tid >> 6] = hi; red[4 + (tid >> 6)] = lo; }
+    __syncthreads();
+    hi = red[0]; lo = red[4];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) { hi = red[w] > hi ? red[w] : hi; lo = red[4 + w] < lo ? red[4 + w] : lo; }
+    const float scale = 256.f / ((float)(hi - lo) + 1.f);
+    int mb = (int)((float)(hi - tmax) * scale);
+    mb = mb > kThreads - 1 ? kThreads - 1 : mb;
+    atomicAdd(&sh.mcount[mb], 1u);
+    __syncthreads();
+    // first bin (from the top) at which k maxima have been seen
+    unsigned long long total;
+    const unsigned long long mine = sh.mcount[tid];
+    const unsigned long long excl = block_excl_scan(mine, sh.wave_tot, total);
+    if (excl < (unsigned long long)top_k && excl + mine >= (unsigned long long)top_k) sh.pick = (uint32_t)tid;
+    if (tid == 0) sh.lkey = 0xffffffffu;
+    __syncthreads();
+    uint32_t l = mb <= (int)sh.pick ? tmax : 0xffffffffu;
+    l = wave_reduce_umin(l);
+    if ((tid & 63) == 0) atomicMin(&sh.lkey, l);
+    __syncthreads();
+    return sh.lkey;
+}
+
+// ... second half: the table holds every logit at or above that bound (ncand of them, no more than the table
+// takes); the one with exactly k-1 ahead of it is the k-th largest logit.
+__device__ __forceinline__ uint32_t kth_of_candidates(Resident &sh, uint32_t ncand, int32_t top_k)
+{
+    for (uint32_t c = threadIdx.x; c < ncand; c += kThreads) {
+        const uint32_t my = sh.ckey[c];
+        uint32_t ahead = 0;
+        for (uint32_t j = 0; j < ncand; ++j) {
+            const uint32_t o = sh.ckey[j];
+            ahead += (o > my || (o == my && j < c)) ? 1u : 0u;
+        }
+        if (ahead == (uint32_t)top_k - 1u) sh.pick = my;
+    }
+    __syncthreads();
+    const uint32_t key = sh.pick;
+    __syncthreads();
+    return key;
+}
+
+// Exact end of a selection by weight: candidates c < ncand with key ckey[c] and integer weight cq[c] (0: not in
+// the running), `before` the weight of everything above all of them.  The group of equal keys at which the
+// running weight, from the largest key down, reaches `need` is the one that closes the selection; returns its
+// key (or thr_key if that is larger).
+__device__ __forceinline__ uint32_t closing_group(Resident &sh, uint32_t ncand, unsigned long long before, double need,
+                                                  uint32_t thr_key)
+{
+    for (uint32_t c = threadIdx.x; c < ncand; c += kThreads) {
+        const uint32_t my = sh.ckey[c];
+        if (sh.cq[c] == 0) continue;
+        unsigned long long above = before, group = 0;
+        for (uint32_t j = 0; j < ncand; ++j) {
+            const uint32_t o = sh.ckey[j];
+            const unsigned long long q = sh.cq[j];
+            above += o > my ? q : 0ull;
+            group += o == my ? q : 0ull;
+        }
+        if (!((double)above >= need) && (double)(above + group) >= need) sh.pick = my;
+    }
+    __syncthreads();
+    const uint32_t pkey = sh.pick;
+    __syncthreads();
+    return pkey > thr_key ? pkey : thr_key;
+}
+
+// The nucleus over the survivors of top-k, all of which are in the candidate table: their masses against the
+// reference of the largest of them, then the closing group.
+template <class K>
+__device__ __forceinline__ uint32_t nucleus_on_candidates(Resident &sh, uint32_t ncand, uint32_t thr_key, float k,
+                                                          float top_p)
+{
+    const int tid = threadIdx.x;
+    float m = -__builtin_inff();
+    for (uint32_t c = tid; c < ncand; c += kThreads)
+        if (sh.ckey[c] >= thr_key) m = fmaxf(m, K::from_key(sh.ckey[c]));
+    m = wave_max(m);
+    float *fred = reinterpret_cast<float *>(sh.hist);
+    if ((tid & 63) == 0) fred[tid >> 6] = m;
+    __syncthreads();
+    m = fred[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
+    const float nr = -fmaxf(ceilf(m * k), -100000.f);
+    unsigned long long local = 0, total;
+    for (uint32_t c = tid; c < ncand; c += kThreads) {
+        const uint32_t key = sh.ckey[c];
+        const unsigned long long q = key >= thr_key ? mass_q(K::from_key(key), k, nr) : 0ull;
+        sh.cq[c] = (uint32_t)q;                 // 0 also takes the candidates below the threshold out
+        local += q;
+    }
+    block_excl_scan(local, sh.wave_tot, total);
+    __syncthreads();
+    return closing_group(sh, ncand, 0ull, (double)top_p * (double)total, thr_key);
+}
+
+// After the masses (or counts) of a whole row have gone into the coarse bins: the first bin, from the top, at
+// which the running weight reaches goal(total).  Leaves that bin in sh.pick (if any bin gets there) and
+// returns the weight above it and, through `need`, the goal.
+template <class Goal>
+__device__ __forceinline__ unsigned long long bin_that_reaches(Resident &sh, Goal goal, double &need)
+{
+    const int tid = threadIdx.x;
+    constexpr int kPer = kCoarseBins / kThreads;
+    unsigned long long local = 0, total;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) local += sh.hist[tid * kPer + i];
+    const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
+    need = goal(total);
+    if (!((double)excl >= need) && (double)(excl + local) >= need) {
+        unsigned long long acc = excl;
+        for (int i = 0; i < kPer; ++i) {
+            const unsigned long long h = sh.hist[tid * kPer + i];
+            if ((double)(acc + h) >= need) {
+                sh.pick = (uint32_t)(tid * kPer + i);
+                // weight above the bin, split over two words of the (still free) candidate key table
+                sh.ckey[kCandCap - 2] = (uint32_t)acc;
+                sh.ckey[kCandCap - 1] = (uint32_t)(acc >> 32);
+                break;
+            }
+            acc += h;
+        }
+    }
+    __syncthreads();
+    const unsigned long long before =
+        (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
+    __syncthreads();
+    return before;
+}
+
 // STEP: go on and finish the sampling step for the row, which is then not read a second time.  With HAS_K from
 // the candidate table (after top-k every kept logit is in it); with the nucleus alone, where most of the row
 // can be kept, from the registers (bf16 rows: their 4096 sums of 8 logits take the histogram's place in LDS).
@@ -443,34 +588,7 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
 #pragma unroll
                 for (int i = 0; i < 4; ++i) tmax = pc[p][i] > tmax ? pc[p][i] : tmax;
         }
-        sh.mcount[tid] = 0;
-        if (tid == 0) sh.ncand = 0;
-        // range of the maxima -> 256 even bins over it, bin 0 the highest
-        uint32_t hi = wave_reduce_umax(tmax), lo = wave_reduce_umin(tmax);
-        uint32_t *red = reinterpret_cast<uint32_t *>(sh.hist);
-        if ((tid & 63) == 0) { red[tid >> 6] = hi; red[4 + (tid >> 6)] = lo; }
-        __syncthreads();
-        hi = red[0]; lo = red[4];
-#pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) { hi = red[w] > hi ? red[w] : hi; lo = red[4 + w] < lo ? red[4 + w] : lo; }
-        const float scale = 256.f / ((float)(hi - lo) + 1.f);
-        int mb = (int)((float)(hi - tmax) * scale);
-        mb = mb > kThreads - 1 ? kThreads - 1 : mb;
-        atomicAdd(&sh.mcount[mb], 1u);
-        __syncthreads();
-        // first bin (from the top) at which k maxima have been seen
-        unsigned long long total;
-        const unsigned long long mine = sh.mcount[tid];
-        const unsigned long long excl = block_excl_scan(mine, sh.wave_tot, total);
-        if (excl < (unsigned long long)top_k && excl + mine >= (unsigned long long)top_k) sh.pick = (uint32_t)tid;
-        if (tid == 0) sh.lkey = 0xffffffffu;
-        __syncthreads();
-        // the lowest maximum in the bins up to there
-        uint32_t l = mb <= (int)sh.pick ? tmax : 0xffffffffu;
-        l = wave_reduce_umin(l);
-        if ((tid & 63) == 0) atomicMin(&sh.lkey, l);
-        __syncthreads();
-        const uint32_t lkey = sh.lkey;
+        const uint32_t lkey = bound_from_thread_maxima(sh, tmax, top_k);
         forget_row();
         auto candidate = [&](uint32_t key, int32_t v) __attribute__((always_inline)) {
             const uint32_t i = atomicAdd(&sh.ncand, 1u);
@@ -520,22 +638,8 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
         }
         __syncthreads();
         ncand = sh.ncand;
-        if (ncand > (uint32_t)kCandCap) {
-            fall = true;
-        } else {
-            // rank the candidates: the one with exactly k-1 ahead of it is the k-th largest logit
-            for (uint32_t c = tid; c < ncand; c += kThreads) {
-                const uint32_t my = sh.ckey[c];
-                uint32_t ahead = 0;
-                for (uint32_t j = 0; j < ncand; ++j) {
-                    const uint32_t o = sh.ckey[j];
-                    ahead += (o > my || (o == my && j < c)) ? 1u : 0u;
-                }
-                if (ahead == (uint32_t)top_k - 1u) sh.pick = my;
-            }
-            __syncthreads();
-            thr_key = sh.pick;
-        }
+        if (ncand > (uint32_t)kCandCap) fall = true;
+        else thr_key = kth_of_candidates(sh, ncand, top_k);
         __syncthreads();
     }
 
@@ -547,27 +651,7 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
         unsigned long long before = 0;
         if (HAS_K) {
             // every survivor of top-k is in the candidate table: work on that
-            float m = -__builtin_inff();
-            for (uint32_t c = tid; c < ncand; c += kThreads)
-                if (sh.ckey[c] >= thr_key) m = fmaxf(m, K::from_key(sh.ckey[c]));
-            m = wave_max(m);
-            float *fred = reinterpret_cast<float *>(sh.hist);
-            if ((tid & 63) == 0) fred[tid >> 6] = m;
-            __syncthreads();
-            m = fred[0];
-#pragma unroll
-            for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
-            const float nr = -fmaxf(ceilf(m * k), -100000.f);
-            unsigned long long local = 0, total;
-            for (uint32_t c = tid; c < ncand; c += kThreads) {
-                const uint32_t key = sh.ckey[c];
-                const unsigned long long q = key >= thr_key ? mass_q(K::from_key(key), k, nr) : 0ull;
-                sh.cq[c] = (uint32_t)q;                 // 0 also takes the candidates below the threshold out
-                local += q;
-            }
-            block_excl_scan(local, sh.wave_tot, total);
-            need = (double)top_p * (double)total;
-            __syncthreads();
+            thr_key = nucleus_on_candidates<K>(sh, ncand, thr_key, k, top_p);
         } else {
             float m = -__builtin_inff();
 #pragma unroll
@@ -622,29 +706,7 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
                 }
             __syncthreads();
             // total, then the first bin (from the top) at which top_p of it is reached
-            constexpr int kPer = kCoarseBins / kThreads;
-            unsigned long long local = 0, total;
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) local += sh.hist[tid * kPer + i];
-            const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
-            need = (double)top_p * (double)total;
-            if (!((double)excl >= need) && (double)(excl + local) >= need) {
-                unsigned long long acc = excl;
-                for (int i = 0; i < kPer; ++i) {
-                    const unsigned long long h = sh.hist[tid * kPer + i];
-                    if ((double)(acc + h) >= need) {
-                        sh.pick = (uint32_t)(tid * kPer + i);
-                        // mass above the bin, split over two words of the (still free) candidate key table
-                        sh.ckey[kCandCap - 2] = (uint32_t)acc;
-                        sh.ckey[kCandCap - 1] = (uint32_t)(acc >> 32);
-                        break;
-                    }
-                    acc += h;
-                }
-            }
-            __syncthreads();
-            before = (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
-            __syncthreads();
+            before = bin_that_reaches(sh, [&](unsigned long long total) { return (double)top_p * (double)total; }, need);
             // the logits of that bin go to the candidate table
             // (second pass over the row: keep the compiler from holding every exponent of the first pass in a
             // register until here)
@@ -735,24 +797,8 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
             ncand = sh.ncand;
             if (ncand > (uint32_t)kCandCap) fall = true;
         }
-        if (!fall) {
-            // rank exactly: the nucleus closes with a whole group of equal logits
-            for (uint32_t c = tid; c < ncand; c += kThreads) {
-                const uint32_t my = sh.ckey[c];
-                if (sh.cq[c] == 0) continue;
-                unsigned long long above = before, group = 0;
-                for (uint32_t j = 0; j < ncand; ++j) {
-                    const uint32_t o = sh.ckey[j];
-                    const unsigned long long q = sh.cq[j];
-                    above += o > my ? q : 0ull;
-                    group += o == my ? q : 0ull;
-                }
-                if (!((double)above >= need) && (double)(above + group) >= need) sh.pick = my;
-            }
-            __syncthreads();
-            const uint32_t pkey = sh.pick;
-            if (pkey > thr_key) thr_key = pkey;
-        }
+        // rank exactly: the nucleus closes with a whole group of equal logits
+        if (!HAS_K && !fall) thr_key = closing_group(sh, ncand, before, need, thr_key);
     }
 
     if (fall) {            // uniform over the block: every thread saw the same counters
@@ -1065,31 +1111,7 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
         // the k-th largest of the thread maxima bounds the k-th largest logit from below
         uint32_t tmax = 0;
         sweep([&](uint32_t key, float) __attribute__((always_inline)) { tmax = umax(tmax, key); });
-        sh.mcount[tid] = 0;
-        if (tid == 0) sh.ncand = 0;
-        uint32_t hi = wave_reduce_umax(tmax), lo = wave_reduce_umin(tmax);
-        uint32_t *red = reinterpret_cast<uint32_t *>(sh.hist);
-        if ((tid & 63) == 0) { red[tid >> 6] = hi; red[4 + (tid >> 6)] = lo; }
-        __syncthreads();
-        hi = red[0]; lo = red[4];
-#pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) { hi = umax(hi, red[w]); lo = red[4 + w] < lo ? red[4 + w] : lo; }
-        const float scale = 256.f / ((float)(hi - lo) + 1.f);
-        int mb = (int)((float)(hi - tmax) * scale);
-        mb = mb > kThreads - 1 ? kThreads - 1 : mb;
-        atomicAdd(&sh.mcount[mb], 1u);
-        __syncthreads();
-        unsigned long long total;
-        const unsigned long long mine = sh.mcount[tid];
-        const unsigned long long excl = block_excl_scan(mine, sh.wave_tot, total);
-        if (excl < (unsigned long long)top_k && excl + mine >= (unsigned long long)top_k) sh.pick = (uint32_t)tid;
-        if (tid == 0) sh.lkey = 0xffffffffu;
-        __syncthreads();
-        uint32_t l = mb <= (int)sh.pick ? tmax : 0xffffffffu;
-        l = wave_reduce_umin(l);
-        if ((tid & 63) == 0) atomicMin(&sh.lkey, l);
-        __syncthreads();
-        const uint32_t lkey = sh.lkey;
+        const uint32_t lkey = bound_from_thread_maxima(sh, tmax, top_k);
         sweep([&](uint32_t key, float) __attribute__((always_inline)) {
             if (key >= lkey) {
                 const uint32_t i = atomicAdd(&sh.ncand, 1u);
@@ -1098,21 +1120,8 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
         });
         __syncthreads();
         ncand = sh.ncand;
-        if (ncand > (uint32_t)kCandCap) {
-            fall = true;
-        } else {
-            for (uint32_t c = tid; c < ncand; c += kThreads) {
-                const uint32_t my = sh.ckey[c];
-                uint32_t ahead = 0;
-                for (uint32_t j = 0; j < ncand; ++j) {
-                    const uint32_t o = sh.ckey[j];
-                    ahead += (o > my || (o == my && j < c)) ? 1u : 0u;
-                }
-                if (ahead == (uint32_t)top_k - 1u) sh.pick = my;
-            }
-            __syncthreads();
-            thr_key = sh.pick;
-        }
+        if (ncand > (uint32_t)kCandCap) fall = true;
+        else thr_key = kth_of_candidates(sh, ncand, top_k);
         __syncthreads();
     }
 
@@ -1152,30 +1161,9 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
             __hip_atomic_fetch_add(dst, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         });
         __syncthreads();
-        constexpr int kPer = kCoarseBins / kThreads;
-        unsigned long long local = 0, total;
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) local += sh.hist[tid * kPer + i];
-        const unsigned long long excl = block_excl_scan(local, sh.wave_tot, total);
-        const double need = goal(total);
-        if (!((double)excl >= need) && (double)(excl + local) >= need) {
-            unsigned long long acc = excl;
-            for (int i = 0; i < kPer; ++i) {
-                const unsigned long long h = sh.hist[tid * kPer + i];
-                if ((double)(acc + h) >= need) {
-                    sh.pick = (uint32_t)(tid * kPer + i);
-                    sh.ckey[kCandCap - 2] = (uint32_t)acc;
-                    sh.ckey[kCandCap - 1] = (uint32_t)(acc >> 32);
-                    break;
-                }
-                acc += h;
-            }
-        }
-        __syncthreads();
-        const unsigned long long before =
-            (unsigned long long)sh.ckey[kCandCap - 2] | ((unsigned long long)sh.ckey[kCandCap - 1] << 32);
+        double need;
+        const unsigned long long before = bin_that_reaches(sh, goal, need);
         const int pick_bin = (int)(sh.pick < (uint32_t)kCoarseBins ? sh.pick : (uint32_t)(kCoarseBins - 1));
-        __syncthreads();
         sweep([&](uint32_t key, float x) __attribute__((always_inline)) {
             if (coarse_bin(fmaf(x, k, nr)) == pick_bin) {
                 const unsigned long long q = weigh(key, x);
@@ -1194,22 +1182,7 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
             fall = true;
             return;
         }
-        for (uint32_t c = tid; c < ncand; c += kThreads) {
-            const uint32_t my = sh.ckey[c];
-            if (sh.cq[c] == 0) continue;
-            unsigned long long above = before, group = 0;
-            for (uint32_t j = 0; j < ncand; ++j) {
-                const uint32_t o = sh.ckey[j];
-                const unsigned long long q = sh.cq[j];
-                above += o > my ? q : 0ull;
-                group += o == my ? q : 0ull;
-            }
-            if (!((double)above >= need) && (double)(above + group) >= need) sh.pick = my;
-        }
-        __syncthreads();
-        const uint32_t pkey = sh.pick;
-        if (pkey > thr_key) thr_key = pkey;
-        __syncthreads();
+        thr_key = closing_group(sh, ncand, before, need, thr_key);
     };
 
     if (KMODE == 2) {
@@ -1224,43 +1197,7 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
     } else if (HAS_P && !fall) {
         if (HAS_K) {
             // every survivor of top-k is in the candidate table
-            double need;
-            float m = -__builtin_inff();
-            for (uint32_t c = tid; c < ncand; c += kThreads)
-                if (sh.ckey[c] >= thr_key) m = fmaxf(m, K::from_key(sh.ckey[c]));
-            m = wave_max(m);
-            float *fred = reinterpret_cast<float *>(sh.hist);
-            if ((tid & 63) == 0) fred[tid >> 6] = m;
-            __syncthreads();
-            m = fred[0];
-#pragma unroll
-            for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, fred[w]);
-            const float nr = -fmaxf(ceilf(m * k), -100000.f);
-            unsigned long long local = 0, total;
-            for (uint32_t c = tid; c < ncand; c += kThreads) {
-                const uint32_t key = sh.ckey[c];
-                const unsigned long long q = key >= thr_key ? mass_q(K::from_key(key), k, nr) : 0ull;
-                sh.cq[c] = (uint32_t)q;
-                local += q;
-            }
-            block_excl_scan(local, sh.wave_tot, total);
-            need = (double)top_p * (double)total;
-            __syncthreads();
-            for (uint32_t c = tid; c < ncand; c += kThreads) {
-                const uint32_t my = sh.ckey[c];
-                if (sh.cq[c] == 0) continue;
-                unsigned long long above = 0, group = 0;
-                for (uint32_t j = 0; j < ncand; ++j) {
-                    const uint32_t o = sh.ckey[j];
-                    const unsigned long long q = sh.cq[j];
-                    above += o > my ? q : 0ull;
-                    group += o == my ? q : 0ull;
-                }
-                if (!((double)above >= need) && (double)(above + group) >= need) sh.pick = my;
-            }
-            __syncthreads();
-            const uint32_t pkey = sh.pick;
-            if (pkey > thr_key) thr_key = pkey;
+            thr_key = nucleus_on_candidates<K>(sh, ncand, thr_key, k, top_p);
         } else {
             const float nr = row_reference();
             select(nr, [&](uint32_t, float x) { return mass_q(x, k, nr); },
