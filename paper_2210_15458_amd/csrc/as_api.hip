@@ -248,12 +248,21 @@ as_status as_model_create_bigram(as_model **out, const void *E, const void *U, i
     (void)hipGetDevice(&m->device);
     m->V = V; m->d = d; m->scale = scale; m->wdtype = wdtype; m->E = E;
     const size_t esz = wdtype == AS_BF16 ? 2 : 4;
-    if (hipMalloc(&m->Ut, (size_t)V * d * esz) != hipSuccess) {
+    // rows of Ut are padded with zeros to a whole number of the logits kernel's 256-column tiles, so that its
+    // loader needs no bounds on the rows it requests
+    const size_t vpad = ((size_t)V + 255) / 256 * 256;
+    if (hipMalloc(&m->Ut, vpad * d * esz) != hipSuccess) {
         (void)hipGetLastError();
         delete m;
         return fail(nullptr, AS_ERR_ALLOC, "device allocation of the transposed weights failed");
     }
-    as_status st = launch_transpose(U, m->Ut, d, V, wdtype);
+    as_status st = AS_OK;
+    if (vpad > (size_t)V &&
+        hipMemset(static_cast<unsigned char *>(m->Ut) + (size_t)V * d * esz, 0, (vpad - V) * d * esz) != hipSuccess) {
+        (void)hipGetLastError();
+        st = fail(nullptr, AS_ERR_DEVICE, "clearing the padding of the transposed weights failed");
+    }
+    if (st == AS_OK) st = launch_transpose(U, m->Ut, d, V, wdtype);
     if (st != AS_OK) {
         (void)hipFree(m->Ut);
         delete m;

@@ -120,7 +120,8 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
                                                                  int gm)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kPersistLds];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // uniform: LDS targets stay scalar
     const int wm = wave >> 1, wn = wave & 1;
 
     // Work-groups are handed to the 8 XCDs round-robin, so block b runs on XCD b & 7 and is worker b >> 3 of
@@ -156,12 +157,16 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
 
     // Loader: a stage is 64 chunks of 1 KB (8 tile rows x 128 B); chunk it*8 + wave, it 0..3, is A rows
     // it*64 + rowb, it 4..7 is B rows (it-4)*64 + rowb; a lane always moves logical piece pc of its row.
+    // Every address is a uniform base plus a 32-bit offset per lane: the B offsets never change (Ut is padded
+    // to whole column tiles, so no row needs a bound), the A offsets change with the row tile.
     const uint32_t rowbytes = (uint32_t)d * 2;
     const unsigned char *Eb = reinterpret_cast<const unsigned char *>(E);
     const unsigned char *Ub = reinterpret_cast<const unsigned char *>(Ut);
     const int rowb = wave * 8 + (lane >> 3);
     const uint32_t pcoff = (uint32_t)(((lane & 7) ^ ((rowb >> 1) & 7)) << 4);
-    uint32_t aoff[4];
+    uint32_t aoff[4], boff[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) boff[it] = (uint32_t)(it * 64 + rowb) * rowbytes + pcoff;
     auto load_aoff = [&](int64_t m0) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
@@ -178,11 +183,8 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
             __builtin_amdgcn_global_load_lds((glb_void *)(Eb + (int64_t)st * (PK * 2) + aoff[it]), (lds_void *)dst,
                                              16, 0, 0);
         } else {
-            int64_t n = n0_ + (it - 4) * 64 + rowb;
-            if (n > V - 1) n = V - 1;
-            const uint32_t off = (uint32_t)n * rowbytes + pcoff;
-            __builtin_amdgcn_global_load_lds((glb_void *)(Ub + (int64_t)st * (PK * 2) + off), (lds_void *)dst, 16, 0,
-                                             0);
+            const unsigned char *base = Ub + n0_ * (int64_t)rowbytes + (int64_t)st * (PK * 2);
+            __builtin_amdgcn_global_load_lds((glb_void *)(base + boff[it - 4]), (lds_void *)dst, 16, 0, 0);
         }
     };
 
@@ -274,25 +276,14 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
         for (int s = 0; s < nstages; ++s, ++gs) {
             const int cur = gs & 1, nb = cur ^ 1;
             const uint32_t so = cur * kRing, son = nb * kRing;
-            // Stage s+1 (second half of its chunks, during slice 0) and stage s+2 (first half, during the last
-            // slice) are requested here; past the end of this tile they are stage 0 of the next one.  Stage 1
-            // of a tile is always requested whole before the tile starts.
-            const bool in1 = s + 1 < nstages, in2 = s + 2 < nstages;
-            const bool rd1 = in1 || carry;
-            const bool ld1 = s > 0 && (in1 || carry);
-            const bool ld2 = in2 || (carry && s + 2 == nstages);
-            const int st1 = in1 ? s + 1 : 0, st2 = in2 ? s + 2 : 0;
-            const int64_t nn1 = in1 ? n0 : n0n, nn2 = in2 ? n0 : n0n;
+            // Stage s+2 is requested whole during the last slice of stage s, into the ring slot that stage s
+            // has just left; past the end of this tile it is stage 0 or 1 of the next one.
+            const bool in2 = s + 2 < nstages;
+            const bool ld2 = in2 || carry;
+            const int st2 = in2 ? s + 2 : s + 2 - nstages;
+            const int64_t nn2 = in2 ? n0 : n0n;
             AS_WAIT_FR(xa, xb);
-            AS_RD_A(ya, 0, so, 1); AS_MM(xa, xb, 0, 0); AS_RD_B(yb, 0, so, 1); AS_MM(xa, xb, 0, 1);
-            if (ld1) AS_GL(nn1, st1, nb, 4);
-            AS_RD_B(yb, 1, so, 1); AS_MM(xa, xb, 0, 2); AS_RD_A(ya, 1, so, 1); AS_MM(xa, xb, 0, 3);
-            if (ld1) AS_GL(nn1, st1, nb, 5);
-            AS_RD_B(yb, 2, so, 1); AS_MM(xa, xb, 1, 0); AS_RD_B(yb, 3, so, 1); AS_MM(xa, xb, 1, 1);
-            if (ld1) AS_GL(nn1, st1, nb, 6);
-            AS_MM(xa, xb, 1, 2);
-            if (ld1) AS_GL(nn1, st1, nb, 7);
-            AS_MM(xa, xb, 1, 3);
+            AS_SLICE(xa, xb, ya, yb, so, 1);
             AS_WAIT_FR(ya, yb);
             AS_SLICE(ya, yb, xa, xb, so, 2);
             AS_WAIT_FR(xa, xb);
@@ -306,29 +297,23 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             AS_SB();
-            if (rd1) AS_RD_A(xa, 0, son, 0);
-            AS_MM(ya, yb, 0, 0);
-            if (rd1) AS_RD_B(xb, 0, son, 0);
-            AS_MM(ya, yb, 0, 1);
+            // last slice, with the first fragments of the next stage (read for nothing after the last stage
+            // of the last tile) and, where there is a stage to request, its eight chunks; the MFMAs stay
+            // outside the conditions (a second copy of them costs the accumulators a second set of registers)
+            AS_RD_A(xa, 0, son, 0); AS_MM(ya, yb, 0, 0);
+            AS_RD_B(xb, 0, son, 0); AS_MM(ya, yb, 0, 1);
             if (ld2) AS_GL(nn2, st2, cur, 0);
-            if (rd1) AS_RD_B(xb, 1, son, 0);
-            AS_MM(ya, yb, 0, 2);
-            if (rd1) AS_RD_A(xa, 1, son, 0);
-            AS_MM(ya, yb, 0, 3);
+            AS_RD_B(xb, 1, son, 0); AS_MM(ya, yb, 0, 2);
             if (ld2) AS_GL(nn2, st2, cur, 1);
-            if (rd1) AS_RD_B(xb, 2, son, 0);
-            AS_MM(ya, yb, 1, 0);
-            if (rd1) AS_RD_B(xb, 3, son, 0);
-            AS_MM(ya, yb, 1, 1);
+            AS_RD_A(xa, 1, son, 0); AS_MM(ya, yb, 0, 3);
             if (ld2) AS_GL(nn2, st2, cur, 2);
-            AS_MM(ya, yb, 1, 2);
+            AS_RD_B(xb, 2, son, 0); AS_MM(ya, yb, 1, 0);
             if (ld2) AS_GL(nn2, st2, cur, 3);
+            AS_RD_B(xb, 3, son, 0); AS_MM(ya, yb, 1, 1);
+            if (ld2) { AS_GL(nn2, st2, cur, 4); AS_GL(nn2, st2, cur, 5); }
+            AS_MM(ya, yb, 1, 2);
+            if (ld2) { AS_GL(nn2, st2, cur, 6); AS_GL(nn2, st2, cur, 7); }
             AS_MM(ya, yb, 1, 3);
-            if (carry && !in1) {
-                // last stage: all of the next tile's stage 1 goes into the slot this stage just left
-                AS_GL(n0n, 1, cur, 0); AS_GL(n0n, 1, cur, 1); AS_GL(n0n, 1, cur, 2); AS_GL(n0n, 1, cur, 3);
-                AS_GL(n0n, 1, cur, 4); AS_GL(n0n, 1, cur, 5); AS_GL(n0n, 1, cur, 6); AS_GL(n0n, 1, cur, 7);
-            }
         }
 
         // ---- epilogue: scale, round once to the storage type, transpose through this wave's 32 x 128 B of
