@@ -126,6 +126,12 @@ as_status as_ctx_profile_samples(as_ctx *ctx, int kernel, float *ms_out,
  *               mass (after top-k) reaches top_p, whole groups; <= 0 or >= 1: off
  *   tokens_out  DEVICE int32[rows]
  *   codes_out   DEVICE float[rows]; may be the same pointer as codes
+ *
+ * Errors in the data on the device (NaN or infinite logits, a row without a
+ * finite logit, codes outside [0,1)) are not detected, no call reads device
+ * data back.  What such a row returns is unspecified but stays in range:
+ * tokens_out in [0, V), codes_out in [0, 1 - 2^-24]; nothing outside the
+ * buffers described here is read or written.
  */
 as_status as_step(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
                   const float *codes, float temp, int32_t top_k, float top_p,
@@ -187,7 +193,8 @@ as_status as_model_destroy(as_model *model);
  * logits_out[r, :] = model logits given prev[r], for r < rows (AS_BF16 weights
  * use bf16 MFMA with fp32 accumulation; the result is rounded once to the ctx
  * logits dtype).
- *   prev        DEVICE int32[rows], each in [0,V)
+ *   prev        DEVICE int32[rows], each in [0,V) (a value outside is not
+ *               detected; the nearest valid token is used instead)
  *   logits_out  DEVICE [rows, ld], ld >= V; columns V..ld-1 are left untouched
  */
 as_status as_bigram_logits(as_ctx *ctx, const as_model *model,
@@ -199,7 +206,8 @@ as_status as_bigram_logits(as_ctx *ctx, const as_model *model,
  * codes from as_lattice, then T times { logits from the model given the
  * previous token; as_step_ex with EOS kept sticky }.  Exactly the sequence of
  * the exported calls above, enqueued back to back with no host round trip.
- *   prompts     DEVICE int32[B]: the token every code of prompt b starts from
+ *   prompts     DEVICE int32[B]: the token every code of prompt b starts from,
+ *               each in [0,V) (as `prev` above)
  *   u           DEVICE float[B]
  *   tokens_out  DEVICE int32[B, N, T]
  *   codes_out   DEVICE float[B, N] final codes, or NULL

@@ -186,6 +186,10 @@ as_status launch_bigram_logits(as_ctx *ctx, const as_model *m, const int32_t *pr
 constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
 constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
 
+// A conditioning token as a row index of the embedding: tokens the library emits are in [0, V); one handed in
+// from outside that is not (a prompt) is clamped rather than followed out of the table.
+__device__ __forceinline__ int32_t clamp_token(int32_t t, int32_t V) { return t < 0 ? 0 : (t > V - 1 ? V - 1 : t); }
+
 template <int CTRL, int ROW_MASK = 0xf>
 __device__ __forceinline__ int dpp_i32(int old, int src)
 {

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void fused_sample_kernel(FusedArgs a)
         }
     }
     const float c = a.codes[r];
-    const int32_t prev = a.prev[r];
+    const int32_t prev = clamp_token(a.prev[r], a.V);
     if (a.finished_in != nullptr && a.finished_in[r] != 0) {
         if (threadIdx.x == 0) {
             a.tokens_out[r * a.tok_stride] = a.eos_id;

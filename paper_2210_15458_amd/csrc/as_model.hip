@@ -172,7 +172,7 @@ __global__ __launch_bounds__(512, 1) void bigram_gemm_persistent(const uint16_t 
         for (int it = 0; it < 4; ++it) {
             int64_t m = m0 + it * 64 + rowb;
             if (m > R - 1) m = R - 1;
-            aoff[it] = (uint32_t)prev[m] * rowbytes + pcoff;
+            aoff[it] = (uint32_t)clamp_token(prev[m], V) * rowbytes + pcoff;
         }
     };
     // request chunk `it` of K stage `st` of the tile whose columns start at n0_ into ring slot buf_
@@ -506,7 +506,7 @@ __global__ __launch_bounds__(256, 2) void bigram_gemm_bf16(const uint16_t *__res
     for (int i = 0; i < 4; ++i) {
         int64_t m = m0 + prow + i * 32;
         if (m > R - 1) m = R - 1;
-        gA[i] = E + (int64_t)prev[m] * d + pc * 8;
+        gA[i] = E + (int64_t)clamp_token(prev[m], V) * d + pc * 8;
     }
 #pragma unroll
     for (int i = 0; i < kBPieces; ++i) {
@@ -618,7 +618,7 @@ __global__ __launch_bounds__(256) void bigram_dot(const WT *__restrict__ E, cons
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= R * V) return;
     const int64_t r = idx / V, v = idx % V;
-    const WT *a = E + (int64_t)prev[r] * d, *b = Ut + v * d;
+    const WT *a = E + (int64_t)clamp_token(prev[r], V) * d, *b = Ut + v * d;
     float acc = 0.f;
     for (int k = 0; k < d; ++k) acc = fmaf(widen(a[k]), widen(b[k]), acc);
     C[r * ldc + v] = to_out<OutT>(acc * alpha);

@@ -1030,6 +1030,13 @@ __global__ __launch_bounds__(kThreads) void threshold_resident_kernel(const void
             o.c_next = rescale_code(tau, lo, ev);
             o.prob = (float)(ev / S);
             o.f_lo = (float)(lo / S);
+            if (sh.cidx[win] == 0xffffffffu) {
+                // no kept candidate with weight: cannot happen for finite logits; leave a valid row behind
+                o.token = 0;
+                o.c_next = rescale_code(0.0, 0.0, 1.0);
+                o.prob = 0.f;
+                o.f_lo = 0.f;
+            }
             write_row(sa, r, o);
         }
     }

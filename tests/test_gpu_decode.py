@@ -305,3 +305,54 @@ def test_wide_lattice_first_step_counts_and_monotonicity():
         assert distinct <= changes
     ctx.close()
     model.close()
+
+
+def test_decode_hostile_data_stays_in_bounds():
+    """Errors in device data are not detected, but nothing leaves its range: weights with NaN and infinities,
+    shifts and uniforms outside [0, 1), prompts outside the vocabulary (clamped) -- through the plain, the fused
+    and the ancestral decode, bf16 and fp32 logits, with and without truncation."""
+    import torch
+    from paper_2210_15458_amd import binding as B
+    from gpu_util import to_dev_logits
+    V, d, Bn, N, T = 5003, 128, 6, 40, 5
+    E, U = synth.bigram_weights(V, d, seed=3, dtype="bf16")
+    Ef, Uf = synth.bf16_bits_to_f32(E), synth.bf16_bits_to_f32(U)
+    rng = np.random.default_rng(5)
+    Ef[rng.integers(0, V, 40), rng.integers(0, d, 40)] = np.nan
+    Ef[rng.integers(0, V, 40), rng.integers(0, d, 40)] = np.inf
+    Uf[rng.integers(0, d, 40), rng.integers(0, V, 40)] = -np.inf
+    Uf[:, 77] = np.nan
+    Ed, Ud = to_dev_logits(synth.f32_to_bf16_bits(Ef)), to_dev_logits(synth.f32_to_bf16_bits(Uf))
+    model = B.Model(Ed, Ud, scale=3.0)
+    prompts = torch.tensor([0, V - 1, V, -1, 2 ** 31 - 1, 17], dtype=torch.int32, device="cuda")
+    u = torch.tensor([0.5, 1.0, 2.5, -0.5, float("nan"), float("inf")], dtype=torch.float32, device="cuda")
+    unif = torch.from_numpy(rng.random((T, Bn * N)).astype(np.float32)).cuda()
+    unif[0, ::7] = float("nan")
+    unif[1, ::5] = 3.0
+    unif[2, ::3] = -1.0
+    for ldtype in (torch.bfloat16, torch.float32):
+        ctx = B.Ctx(Bn * N, V, ldtype)
+        for top_k, top_p in [(0, 1.0), (40, 1.0), (0, 0.9), (7, 0.6)]:
+            print("case hostile decode", ldtype, top_k, top_p, flush=True)
+            tok = torch.full((Bn, N, T), -7, dtype=torch.int32, device="cuda")
+            cf = torch.full((Bn * N,), -1.0, dtype=torch.float32, device="cuda")
+            B.as_decode(ctx, model, prompts, N, T, u, 1.0, top_k, top_p, 1, tok, cf)
+            torch.cuda.synchronize()
+            t, c = tok.cpu().numpy(), cf.cpu().numpy()
+            assert ((t >= 0) & (t < V)).all()
+            assert np.isfinite(c).all() and (c >= 0).all() and (c <= np.float32(1.0) - np.float32(2.0 ** -24)).all()
+            tok.fill_(-7)
+            B.as_decode_ancestral(ctx, model, prompts, N, T, unif, 1.0, top_k, top_p, 1, tok)
+            torch.cuda.synchronize()
+            t = tok.cpu().numpy()
+            assert ((t >= 0) & (t < V)).all()
+        if ldtype == torch.bfloat16:
+            print("case hostile fused decode", flush=True)
+            tok = torch.full((Bn, N, T), -7, dtype=torch.int32, device="cuda")
+            cf = torch.full((Bn * N,), -1.0, dtype=torch.float32, device="cuda")
+            B.as_decode_fused(ctx, model, prompts, N, T, u, 0.8, 1, tok, cf)
+            torch.cuda.synchronize()
+            t, c = tok.cpu().numpy(), cf.cpu().numpy()
+            assert ((t >= 0) & (t < V)).all()
+            assert np.isfinite(c).all() and (c >= 0).all() and (c <= np.float32(1.0) - np.float32(2.0 ** -24)).all()
+        ctx.close()

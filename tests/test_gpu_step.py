@@ -183,6 +183,49 @@ def test_step_truncation_multi_tile():
     _check(256000, 6, "bf16", top_p=0.9, seed=34)
 
 
+def _hostile_rows(V, dtype, seed):
+    """Rows and codes that break the contract on purpose (NaN, +inf, nothing finite, values near the largest
+    float; codes outside [0, 1)): what comes back is undefined, but it must stay inside its bounds."""
+    rng = np.random.default_rng(seed)
+    R = 16
+    x = (rng.standard_normal((R, V)) * 3.0).astype(np.float32)
+    nan, inf = np.float32(np.nan), np.float32(np.inf)
+    x[0, :] = nan
+    x[1, rng.integers(0, V, max(1, V // 50))] = nan
+    x[2, rng.integers(0, V, min(3, V))] = inf
+    x[3, :] = -inf
+    x[4, :] = np.where(rng.random(V) < 0.5, np.float32(3.0e38), np.float32(-3.0e38))
+    x[5, :] = inf
+    x[6, ::2] = nan
+    x[6, 1::2] = inf
+    x[7, :] = -inf
+    x[7, V // 2] = nan
+    x[8, 0] = inf
+    x[8, V - 1] = -inf
+    codes = rng.random(R).astype(np.float32)
+    codes[9], codes[10], codes[11], codes[12], codes[13] = 1.0, 2.5, -0.5, nan, inf
+    stored = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    return stored, codes
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V", [7, 1001, 32128, 50257])
+def test_step_hostile_inputs_stay_in_bounds(V, dtype):
+    """Data errors are not detected, but every path keeps its outputs in range: tokens in [0, V), the next code
+    in [0, 1 - 2^-24], flags 0 or 1 (resident, fused and streamed truncation kernels, whole-vector and
+    partial-vector rows, extreme temperatures)."""
+    from gpu_util import run_gpu_step
+    stored, codes = _hostile_rows(V, dtype, seed=V)
+    for temp, top_k, top_p in [(1.0, 0, 1.0), (0.7, 40, 1.0), (1.0, 0, 0.9), (1.0, 5, 0.5), (1.0, 300, 0.95),
+                               (1e-38, 0, 1.0), (1e38, 0, 0.9), (1e-30, 3, 0.7)]:
+        print("case hostile", V, dtype, temp, top_k, top_p, flush=True)
+        out = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, eos_id=1)
+        tok, c = out["token"], out["c_next"]
+        assert ((tok >= 0) & (tok < V)).all(), (temp, top_k, top_p, tok)
+        assert np.isfinite(c).all() and (c >= 0.0).all() and (c <= np.float32(1.0) - np.float32(2.0 ** -24)).all(), c
+        assert np.isin(out["finished"], (0, 1)).all()
+
+
 def test_step_argument_errors():
     import torch
     from paper_2210_15458_amd import binding as B
