@@ -356,3 +356,41 @@ def test_decode_hostile_data_stays_in_bounds():
             assert ((t >= 0) & (t < V)).all()
             assert np.isfinite(c).all() and (c >= 0).all() and (c <= np.float32(1.0) - np.float32(2.0 ** -24)).all()
         ctx.close()
+
+
+@pytest.mark.parametrize("top_k,top_p", [(0, 1.0), (40, 0.9)])
+def test_decode_on_side_streams_matches_default_stream(top_k, top_p):
+    """A context works on the stream it was made with and on nothing else: two contexts on two streams (default
+    priority), half of the prompts each and in flight together, give token for token what one context on the
+    default stream gives for all of them (rows are independent and every kernel is deterministic)."""
+    import torch
+    from paper_2210_15458_amd import binding as B
+    V, d, Bn, N, T = 32128, 512, 4, 64, 6
+    _, _, model = _upload_model(V, d, "bf16")
+    prompts = torch.from_numpy(synth.prompts(Bn, V, seed=1)).cuda()
+    u = torch.from_numpy(synth.shifts(Bn, seed=2)).cuda()
+    ctx = B.Ctx(Bn * N, V, torch.bfloat16)
+    ref = torch.empty((Bn, N, T), dtype=torch.int32, device="cuda")
+    ref_c = torch.empty(Bn * N, dtype=torch.float32, device="cuda")
+    B.as_decode(ctx, model, prompts, N, T, u, 0.9, top_k, top_p, 1, ref, ref_c)
+    torch.cuda.synchronize()
+    ctx.close()
+    h = Bn // 2
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs = [B.Ctx(h * N, V, torch.bfloat16, stream=st) for st in streams]
+    ps = [prompts[:h].contiguous(), prompts[h:].contiguous()]
+    us = [u[:h].contiguous(), u[h:].contiguous()]
+    toks = [torch.full((h, N, T), -7, dtype=torch.int32, device="cuda") for _ in range(2)]
+    cfs = [torch.full((h * N,), -1.0, dtype=torch.float32, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(3):                                 # several rounds, both streams busy at once
+        for i in range(2):
+            B.as_decode(ctxs[i], model, ps[i], N, T, us[i], 0.9, top_k, top_p, 1, toks[i], cfs[i])
+    for st in streams:
+        st.synchronize()
+    got = torch.cat(toks, dim=0).cpu().numpy()
+    got_c = torch.cat(cfs, dim=0).cpu().numpy()
+    for c in ctxs:
+        c.close()
+    assert (got == ref.cpu().numpy()).all()
+    assert (got_c == ref_c.cpu().numpy()).all()
