@@ -394,3 +394,44 @@ def test_decode_on_side_streams_matches_default_stream(top_k, top_p):
         c.close()
     assert (got == ref.cpu().numpy()).all()
     assert (got_c == ref_c.cpu().numpy()).all()
+
+
+@pytest.mark.parametrize("top_k,top_p", [(0, 1.0), (40, 0.9)])
+def test_decode_captured_in_a_graph_replays_like_eager(top_k, top_p):
+    """Once its workspace exists (first call), as_decode allocates nothing, waits for nothing and reads nothing
+    back, so a stream capture takes it whole.  Every replay, with fresh shifts written into the same buffer and
+    eager work of the same context in between, gives what the eager call gives for those shifts."""
+    import torch
+    from paper_2210_15458_amd import binding as B
+    V, d, Bn, N, T = 32128, 512, 4, 32, 5
+    _, _, model = _upload_model(V, d, "bf16")
+    prompts = torch.from_numpy(synth.prompts(Bn, V, seed=1)).cuda()
+    u = torch.from_numpy(synth.shifts(Bn, seed=2)).cuda()
+    side = torch.cuda.Stream()
+    ctx = B.Ctx(Bn * N, V, torch.bfloat16, stream=side)
+    tok = torch.full((Bn, N, T), -7, dtype=torch.int32, device="cuda")
+    cf = torch.full((Bn * N,), -1.0, dtype=torch.float32, device="cuda")
+    etok, ecf = torch.empty_like(tok), torch.empty_like(cf)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        B.as_decode(ctx, model, prompts, N, T, u, 0.9, top_k, top_p, 1, tok, cf)      # makes the workspace
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.as_decode(ctx, model, prompts, N, T, u, 0.9, top_k, top_p, 1, tok, cf)
+    side.synchronize()
+    for rep in range(4):
+        new_u = torch.from_numpy(synth.shifts(Bn, seed=10 + rep)).cuda()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            u.copy_(new_u)
+            tok.fill_(-7)
+            graph.replay()
+        side.synchronize()
+        got, got_c = tok.cpu().numpy().copy(), cf.cpu().numpy().copy()
+        with torch.cuda.stream(side):
+            B.as_decode(ctx, model, prompts, N, T, new_u, 0.9, top_k, top_p, 1, etok, ecf)     # eager, same context
+        side.synchronize()
+        assert (got == etok.cpu().numpy()).all(), rep
+        assert (got_c == ecf.cpu().numpy()).all(), rep
+    ctx.close()
