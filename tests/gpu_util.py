@@ -89,7 +89,7 @@ def compare_step(gpu, ref, V, label="", trunc=False):
     strict = dc <= 1e-5 * np.maximum(ref["c_next"][ok], 1e-30) + 2.0 ** -24
     return dict(rows=len(tok_o), mismatches=int(mism.sum()), boundary=int((mism & near).sum()),
                 nucleus=int((mism & nuc & ~near).sum()), nucleus_rows=int(np.sum(nuc)), in_band=int(near.sum()),
-                code_within_1e5_rel=float(strict.mean()), worst_dc_times_p=float((dc * p).max(initial=0.0)),
+                code_within_1e5_rel=float(strict.mean()) if strict.size else 1.0, worst_dc_times_p=float((dc * p).max(initial=0.0)),
                 worst_rel_p=float(rel_p.max(initial=0.0)))
 
 

@@ -178,6 +178,19 @@ def test_step_three_pass_kernel(monkeypatch):
     _check(32128, 8, "bf16", top_p=0.9, seed=43)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V", [1 << 21, (1 << 21) - 5])
+def test_step_maximum_vocab(V, dtype):
+    """The largest vocabulary the library takes (AS_MAX_VOCAB): 64 tiles per bf16 row and 128 per fp32 row, so
+    a lane of the deciding wave walks several shares; the ragged size has rows that start off 16 bytes."""
+    _check(V, 3, dtype, seed=21)
+    _check(V, 3, dtype, temp=0.8, top_k=40, seed=22)
+    # (a peaked row: with two million near-equal fp32 probabilities every nucleus closes within the band of
+    # top_p and the comparison would excuse all of it)
+    _, _, stats = _check(V, 3, dtype, top_p=0.9, sigma=8.0, seed=23)
+    assert stats["nucleus_rows"] < 3
+
+
 def test_step_truncation_multi_tile():
     _check(256000, 6, "bf16", top_k=40, seed=33)
     _check(256000, 6, "bf16", top_p=0.9, seed=34)
