@@ -61,7 +61,9 @@ _GEMM_CASES = [
     # ... sixteen row tiles: the workers of an XCD stand 8 x 4 over row and column tiles, two row tiles each
     (9000, 128, "bf16", "bf16", 4096, 0, 0),
     # the tile kernel on the headline shape
-    (32128, 512, "bf16", "bf16", 130, 0, 1), (32128, 512, "bf16", "f32", 40, 0, 1)]
+    (32128, 512, "bf16", "bf16", 130, 0, 1), (32128, 512, "bf16", "f32", 40, 0, 1),
+    # the largest vocabulary the library takes: 8192 column tiles
+    (1 << 21, 128, "bf16", "bf16", 260, 0, 0)]
 
 
 @pytest.mark.parametrize("gm", [32, 4, 1])

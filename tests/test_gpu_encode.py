@@ -38,13 +38,13 @@ _INTERVAL_CASES = (
     [(dt, V, ld, *m) for dt in ("bf16", "f32") for (V, ld) in [(32128, None), (1001, None), (1001, 1008), (5, None)]
      for m in _MODS]
     + [(dt, V, None, *m) for dt in ("bf16", "f32") for V in (12000, 16384, 16392) for m in _MODS[:2]]
-    + [("bf16", 256000, None, 1.0, 0, 1.0)])
+    + [("bf16", 256000, None, 1.0, 0, 1.0), ("bf16", 1 << 21, None, 1.0, 0, 1.0), ("f32", (1 << 21) - 5, None, 0.8, 40, 1.0)])
 
 
 @pytest.mark.parametrize("dtype,V,ld,temp,top_k,top_p", _INTERVAL_CASES)
 def test_interval_step_matches_oracle(dtype, V, ld, temp, top_k, top_p):
     import oracle
-    R = 24 if V > 100000 else 48
+    R = 8 if V > 1000000 else (24 if V > 100000 else 48)
     stored = synth.gaussian_logits(R, V, sigma=3.0, seed=V + 5, dtype=dtype, ld=ld)
     rng = np.random.default_rng(V)
     # half the tokens where the mass is (decoded from uniform codes), half anywhere
