@@ -150,6 +150,7 @@ as_status as_step(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
  *   flo_out       DEVICE float[rows] or NULL: F(v-1), start of its interval
  *   row_ids       DEVICE int32[rows] or NULL: logits row read by each code
  *                 (several codes may share a row), each in [0, logits_rows)
+ *                 (an index outside is not detected; the nearest row is read)
  *   logits_rows   number of rows in `logits` when row_ids is given
  */
 as_status as_step_ex(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,

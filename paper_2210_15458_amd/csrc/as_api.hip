@@ -64,6 +64,28 @@ static as_status grow(as_ctx *ctx, DeviceBuf &b, size_t bytes)
     return AS_OK;
 }
 
+// Row indices handed in by the caller, as the kernels use them: a copy in the context's workspace with every
+// index brought into [0, logits_rows) (an index outside is a caller's error that no call can report, since
+// none reads device data back; it must not send a kernel outside the logits).
+__global__ void row_ids_in_range_kernel(const int32_t *in, int32_t *out, int64_t n, int64_t logits_rows)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t v = in[i];
+    out[i] = (int32_t)(v < 0 ? 0 : (v > logits_rows - 1 ? logits_rows - 1 : v));
+}
+
+static as_status row_ids_in_range(as_ctx *ctx, const int32_t *&row_ids, int64_t rows, int64_t logits_rows)
+{
+    if (!row_ids) return AS_OK;
+    const int64_t top = logits_rows < 0x7fffffffLL ? logits_rows : 0x7fffffffLL;
+    hipLaunchKernelGGL(row_ids_in_range_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, ctx->stream,
+                       row_ids, ctx->rid, rows, top);
+    AS_HIP_TRY(ctx, hipGetLastError());
+    row_ids = ctx->rid;
+    return AS_OK;
+}
+
 static bool truncation_on(int32_t V, int32_t top_k, float top_p)
 {
     return (top_k > 0 && top_k < V) || (top_p > 0.f && top_p < 1.f);
@@ -120,8 +142,10 @@ as_status as_ctx_create(as_ctx **out, int64_t max_rows, int32_t V, as_dtype logi
         return hip_fail(nullptr, e, "hipDeviceGetAttribute");
     }
     e = hipMalloc(reinterpret_cast<void **>(&c->thr), (size_t)max_rows * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&c->rid), (size_t)max_rows * sizeof(int32_t));
     if (e != hipSuccess) {
         (void)hipGetLastError();
+        if (c->thr) (void)hipFree(c->thr);
         delete c;
         return fail(nullptr, AS_ERR_ALLOC, "device allocation of the context workspace failed");
     }
@@ -134,6 +158,7 @@ as_status as_ctx_destroy(as_ctx *ctx)
     if (!ctx) return AS_OK;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->thr) (void)hipFree(ctx->thr);
+    if (ctx->rid) (void)hipFree(ctx->rid);
     if (ctx->logits.ptr) (void)hipFree(ctx->logits.ptr);
     if (ctx->state.ptr) (void)hipFree(ctx->state.ptr);
     for (auto &v : ctx->prof.slots)
@@ -200,6 +225,8 @@ as_status as_step_ex(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, 
         return fail(ctx, AS_ERR_INVALID_ARG, "finished_in given without an eos_id to emit");
     if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
     if (isnan(top_p)) return fail(ctx, AS_ERR_INVALID_ARG, "top_p is NaN");
+    st = row_ids_in_range(ctx, row_ids, rows, logits_rows);
+    if (st != AS_OK) return st;
 
     StepArgs a{};
     a.logits = logits; a.rows = rows; a.ld = ld; a.V = ctx->V; a.dtype = ctx->dtype;
@@ -504,6 +531,7 @@ as_status as_interval_step(as_ctx *ctx, const void *logits, int64_t rows, int64_
         return fail(ctx, AS_ERR_INVALID_ARG, "finished_in given without an eos_id");
     if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
     if (isnan(top_p)) return fail(ctx, AS_ERR_INVALID_ARG, "top_p is NaN");
+    if (as_status st = row_ids_in_range(ctx, row_ids, rows, logits_rows); st != AS_OK) return st;
 
     const float *thr = nullptr;
     if (truncation_on(ctx->V, top_k, top_p)) {

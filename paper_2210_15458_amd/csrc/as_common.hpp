@@ -48,6 +48,7 @@ struct as_ctx {
     as_dtype dtype = AS_BF16;
     // fixed workspace (allocated at creation): per-row truncation thresholds
     float *thr = nullptr;          // [max_rows]
+    int32_t *rid = nullptr;        // [max_rows] the caller's row_ids brought into range
     // decode workspace (grown on demand by as_decode)
     as::DeviceBuf logits;          // [rows, ld]
     as::DeviceBuf state;           // codes f32[rows] | prev i32[rows] | finished u8[rows]

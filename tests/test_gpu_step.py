@@ -87,6 +87,20 @@ def test_step_finished_rows_eos_and_row_ids():
     assert (gpu["finished"][fin == 0] == 1).any()                          # some row emitted EOS now
 
 
+@pytest.mark.parametrize("top_k,top_p", [(0, 1.0), (40, 1.0), (0, 0.9)])
+def test_step_row_ids_out_of_range_read_the_nearest_row(top_k, top_p):
+    """A row index outside the logits is a caller's error that no call can report; it is brought into range
+    rather than followed: the result is the oracle's for the clamped indices."""
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    V, LR = 32128, 6
+    stored = synth.gaussian_logits(LR, V, seed=31, dtype="bf16")
+    rid = np.array([0, LR - 1, LR, -1, 2 ** 31 - 1, -2 ** 31, 3, 10 ** 6], dtype=np.int32)
+    codes = synth.uniform_codes(rid.size, seed=32)
+    gpu = run_gpu_step(stored, codes, V, top_k=top_k, top_p=top_p, row_ids=rid)
+    ref = oracle_step(stored, codes, V, top_k=top_k, top_p=top_p, row_ids=np.clip(rid.astype(np.int64), 0, LR - 1))
+    print(compare_step(gpu, ref, V, "row_ids out of range", trunc=(top_k > 0 or top_p < 1.0)), flush=True)
+
+
 def test_step_is_deterministic_and_in_place():
     import torch
     from paper_2210_15458_amd import binding as B
