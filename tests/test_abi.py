@@ -62,3 +62,14 @@ def test_product_package_does_not_touch_the_oracle():
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src and "liboracle" not in src, f
                 assert "arith_oracle" not in src, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is one GPU: `bench.py --gpus N` with N > 1 says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert out.returncode != 0
+    assert "one GPU" in (out.stdout + out.stderr)
+    assert "{" not in out.stdout                     # no benchmark line
