@@ -101,6 +101,38 @@ def test_step_row_ids_out_of_range_read_the_nearest_row(top_k, top_p):
     print(compare_step(gpu, ref, V, "row_ids out of range", trunc=(top_k > 0 or top_p < 1.0)), flush=True)
 
 
+@pytest.mark.parametrize("V,dtype,temp,top_k,top_p", [(32128, "bf16", 1.0, 40, 1.0), (32128, "bf16", 1.0, 0, 0.9),
+                                                      (32128, "bf16", 0.7, 200, 0.95), (50257, "f32", 1.0, 40, 1.0),
+                                                      (50257, "f32", 1.0, 0, 0.9), (50257, "bf16", 1.3, 1000, 0.8)])
+def test_lattice_on_a_truncated_row_counts_and_monotonicity(V, dtype, temp, top_k, top_p):
+    """N evenly spaced codes on one row (shared through row_ids), with truncation: every code decodes as the
+    oracle says, tokens are non-decreasing in the code, only kept tokens come out, and each token gets floor or
+    ceil of N times its probability under the truncated distribution (Sec. 4.3; up to the fp32 rounding of the
+    codes and the counted boundary cases)."""
+    import oracle
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    N = 4096
+    stored = synth.gaussian_logits(3, V, seed=V % 1000 + top_k, dtype=dtype)
+    rid = np.full(N, 1, dtype=np.int32)
+    codes = np.minimum(oracle.lattice(N, 0.37).astype(np.float32), np.float32(1 - 2.0 ** -24))
+    gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, row_ids=rid)
+    ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, row_ids=rid.astype(np.int64))
+    stats = compare_step(gpu, ref, V, "lattice on a truncated row", trunc=True)
+    print("   ", stats, flush=True)
+    tok = gpu["token"]
+    assert np.all(np.diff(tok) >= 0)
+    if stats["nucleus_rows"] == 0:                      # (a row whose nucleus closes within the band may keep one group more)
+        p = np.zeros(V)
+        p[ref["token"]] = ref["p"]
+        assert np.all(p[tok] > 0)
+        cnt = np.bincount(tok, minlength=V)
+        seen = cnt > 0
+        eps = 2 * N * 2.0 ** -24 + 1e-9
+        slack = stats["mismatches"]
+        assert np.all(cnt[seen] >= np.floor(N * p[seen] - eps) - slack)
+        assert np.all(cnt[seen] <= np.ceil(N * p[seen] + eps) + slack)
+
+
 def test_step_is_deterministic_and_in_place():
     import torch
     from paper_2210_15458_amd import binding as B
