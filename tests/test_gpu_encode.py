@@ -97,10 +97,12 @@ def _model(V, d, dtype, seed=0):
     return E, U, Ed, model
 
 
-@pytest.mark.parametrize("cfg_id,T", [(0, 8), (1, 3)])
-def test_encode_inverts_decode(cfg_id, T):
+@pytest.mark.parametrize("cfg_id,T,top_k,top_p", [(0, 8, 0, 1.0), (1, 3, 0, 1.0), (1, 3, 40, 1.0), (1, 3, 0, 0.9),
+                                                  (1, 3, 300, 0.8), (0, 8, 5, 0.7)])
+def test_encode_inverts_decode(cfg_id, T, top_k, top_p):
     """The interval of a decoded sequence contains the code it was decoded from (Sec. 4.1), for as long as
-    the interval is wide against the rounding of an fp32 code."""
+    the interval is wide against the rounding of an fp32 code.  With truncation both directions have to keep
+    the same tokens of every row (the decode's fused kernels and the encode's threshold kernel agree)."""
     import torch
     from paper_2210_15458_amd import binding as B
     cfg = synth.CONFIGS[cfg_id]
@@ -116,10 +118,10 @@ def test_encode_inverts_decode(cfg_id, T):
     inside = total = 0
     for t_len in range(1, T + 1):
         tokens = torch.empty((Bn, N, t_len), dtype=torch.int32, device="cuda")
-        B.as_decode(ctx, model, prompts, N, t_len, u, cfg["temp"], 0, 1.0, cfg["eos_id"], tokens)
+        B.as_decode(ctx, model, prompts, N, t_len, u, cfg["temp"], top_k, top_p, cfg["eos_id"], tokens)
         lo = torch.empty(R, dtype=torch.float64, device="cuda")
         w = torch.empty(R, dtype=torch.float64, device="cuda")
-        B.as_encode(ctx, model, prompts, N, t_len, tokens, cfg["temp"], 0, 1.0, cfg["eos_id"], lo, w)
+        B.as_encode(ctx, model, prompts, N, t_len, tokens, cfg["temp"], top_k, top_p, cfg["eos_id"], lo, w)
         torch.cuda.synchronize()
         c = codes0.cpu().numpy().astype(np.float64)
         lo_h, w_h = lo.cpu().numpy(), w.cpu().numpy()
