@@ -33,7 +33,8 @@ def lib():
             C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int32, C.c_void_p,
             C.c_void_p, C.c_double, C.c_int32, C.c_double, C.c_void_p,
             C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+            C.c_int32, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ao_step_rows.restype = C.c_int
         L.ao_bigram_logits.argtypes = [
             C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_double,
@@ -99,9 +100,36 @@ def lattice_paper(N, b):
     return out
 
 
+def _step_call(logits, dt, ld, V, codes, temp, top_k, top_p, fin, eos_id, rid, nthreads, nuc_shift, band):
+    rows = codes.shape[0]
+    out = dict(
+        token=np.empty(rows, np.int32), c_next=np.empty(rows, np.float64),
+        p=np.empty(rows, np.float64), f_lo=np.empty(rows, np.float64),
+        f_hi=np.empty(rows, np.float64), delta=np.empty(rows, np.float64),
+        nuc_margin=np.empty(rows, np.float64), n_kept=np.empty(rows, np.int32),
+        finished=np.empty(rows, np.uint8), nuc_alt=np.empty((rows, 2), np.int32),
+        tok_nb=np.empty((rows, 2), np.int32), p_nb=np.empty((rows, 2), np.float64))
+    rc = lib().ao_step_rows(
+        _ptr(logits), dt, rows, ld, V, _ptr(rid), _ptr(codes), float(temp),
+        int(top_k), float(top_p), _ptr(fin), int(eos_id), _ptr(out["token"]),
+        _ptr(out["c_next"]), _ptr(out["p"]), _ptr(out["f_lo"]),
+        _ptr(out["f_hi"]), _ptr(out["delta"]), _ptr(out["nuc_margin"]),
+        _ptr(out["n_kept"]), _ptr(out["finished"]), int(nthreads),
+        int(nuc_shift), float(band), _ptr(out["nuc_alt"]), _ptr(out["tok_nb"]), _ptr(out["p_nb"]))
+    if rc != 0:
+        raise MemoryError("oracle step failed")
+    return out
+
+
 def step(logits, codes, temp=1.0, top_k=0, top_p=1.0, finished=None,
-         eos_id=-1, row_ids=None, V=None, nthreads=1):
-    """One decode step for every row.  Returns a dict of per-row arrays."""
+         eos_id=-1, row_ids=None, V=None, nthreads=1, band=0.0, nuc_shift=0):
+    """One decode step for every row.  Returns a dict of per-row arrays.
+
+    With band > 0 and the nucleus on, rows whose running mass passes within `band` of top_p at a group end
+    also get the step under every other admissible closing of the nucleus: out["alt"] is a list of
+    (shift, row indices, dict of arrays for those rows), one entry per shift != 0 that some row admits
+    (the C routine is simply called again for those rows with that shift).
+    """
     logits, dt = _stored(logits)
     if logits.ndim == 1:
         logits = logits[None, :]
@@ -111,20 +139,19 @@ def step(logits, codes, temp=1.0, top_k=0, top_p=1.0, finished=None,
     rows = codes.shape[0]
     rid = None if row_ids is None else np.ascontiguousarray(row_ids, dtype=np.int64)
     fin = None if finished is None else np.ascontiguousarray(finished, dtype=np.uint8)
-    out = dict(
-        token=np.empty(rows, np.int32), c_next=np.empty(rows, np.float64),
-        p=np.empty(rows, np.float64), f_lo=np.empty(rows, np.float64),
-        f_hi=np.empty(rows, np.float64), delta=np.empty(rows, np.float64),
-        nuc_margin=np.empty(rows, np.float64), n_kept=np.empty(rows, np.int32),
-        finished=np.empty(rows, np.uint8))
-    rc = lib().ao_step_rows(
-        _ptr(logits), dt, rows, ld, V, _ptr(rid), _ptr(codes), float(temp),
-        int(top_k), float(top_p), _ptr(fin), int(eos_id), _ptr(out["token"]),
-        _ptr(out["c_next"]), _ptr(out["p"]), _ptr(out["f_lo"]),
-        _ptr(out["f_hi"]), _ptr(out["delta"]), _ptr(out["nuc_margin"]),
-        _ptr(out["n_kept"]), _ptr(out["finished"]), int(nthreads))
-    if rc != 0:
-        raise MemoryError("oracle step failed")
+    out = _step_call(logits, dt, ld, V, codes, temp, top_k, top_p, fin, eos_id, rid, nthreads, nuc_shift, band)
+    out["alt"] = []
+    if band > 0.0 and 0.0 < top_p < 1.0 and nuc_shift == 0:
+        lo, hi = out["nuc_alt"][:, 0], out["nuc_alt"][:, 1]
+        src = np.arange(rows, dtype=np.int64) if rid is None else rid
+        for shift in list(range(-int(lo.max(initial=0)), 0)) + list(range(1, int(hi.max(initial=0)) + 1)):
+            idx = np.nonzero((lo >= -shift) if shift < 0 else (hi >= shift))[0]
+            if idx.size == 0:
+                continue
+            sub = _step_call(logits, dt, ld, V, np.ascontiguousarray(codes[idx]), temp, top_k, top_p,
+                             None if fin is None else np.ascontiguousarray(fin[idx]), eos_id,
+                             np.ascontiguousarray(src[idx]), nthreads, shift, band)
+            out["alt"].append((shift, idx, sub))
     return out
 
 

@@ -58,7 +58,31 @@ typedef struct {
                           group that closes the nucleus and at the one
                           before it, whichever is smaller; +inf otherwise */
     int32_t n_kept;    /* tokens with non-zero probability after masking  */
+    int32_t nuc_alt_lo;/* nucleus only: how many closings EARLIER than the
+                          rule's are within `band` of being the rule's (the
+                          running mass at that earlier group is already
+                          within band of top_p); 0 otherwise                */
+    int32_t nuc_alt_hi;/* ... and how many LATER ones (the running mass at
+                          the rule's group, and at the ones after it,
+                          exceeds top_p by less than band)                  */
+    int32_t tok_prev;  /* nearest token before the emitted one that has
+                          non-zero probability, -1 if none                  */
+    int32_t tok_next;  /* nearest such token after it, -1 if none           */
+    double  p_prev;    /* their probabilities (0 if none)                   */
+    double  p_next;
 } ao_step_result;
+
+/* Which nucleus to form.  The rule (shift 0) closes the nucleus with the first
+ * group of equal logits at which the running mass reaches top_p.  An
+ * implementation in finite precision may legitimately close one group earlier
+ * or later when that mass passes within a hair of top_p; `shift` asks for the
+ * kept set that closes that many groups later (negative: earlier), so that a
+ * checker can compare against every admissible alternative, and `band` is the
+ * width of the hair used to count the alternatives. */
+typedef struct {
+    int32_t shift;
+    double  band;
+} ao_nucleus_opt;
 
 /* ------------------------------------------------------------------ */
 /* storage widening                                                    */
@@ -125,9 +149,13 @@ void ao_lattice_paper(int32_t N, double b, double *codes)
 /* Sec. 2 / Sec. 5: logit modifiers -> unnormalised kept weights       */
 /* ------------------------------------------------------------------ */
 
+/* descending; a NaN (no logit at all: outside the method) orders after every
+ * number so that the order stays total */
 static int cmp_desc(const void *a, const void *b)
 {
     double x = *(const double *)a, y = *(const double *)b;
+    int xn = isnan(x), yn = isnan(y);
+    if (xn || yn) return xn - yn;
     return (x < y) - (x > y);
 }
 
@@ -147,17 +175,21 @@ static int cmp_desc(const void *a, const void *b)
  * Returns the sum of e in vocabulary order; writes n_kept and nuc_margin.
  */
 static double kept_weights(const double *x, int32_t V, double temp,
-                           int32_t top_k, double top_p,
+                           int32_t top_k, double top_p, ao_nucleus_opt nuc,
                            double *e, double *scratch,
-                           int32_t *n_kept, double *nuc_margin)
+                           int32_t *n_kept, double *nuc_margin,
+                           int32_t *nuc_alt_lo, int32_t *nuc_alt_hi)
 {
     double thr = -INFINITY;           /* keep x_v >= thr */
     *nuc_margin = INFINITY;
+    *nuc_alt_lo = 0;
+    *nuc_alt_hi = 0;
 
     if (top_k > 0 && top_k < V) {
         memcpy(scratch, x, (size_t)V * sizeof(double));
         qsort(scratch, (size_t)V, sizeof(double), cmp_desc);
         thr = scratch[top_k - 1];
+        if (isnan(thr)) thr = -INFINITY;   /* fewer than k numbers: keep them all */
     }
 
     if (top_p > 0.0 && top_p < 1.0) {
@@ -168,27 +200,47 @@ static double kept_weights(const double *x, int32_t V, double temp,
         int32_t n = 0;
         for (int32_t v = 0; v < V; ++v)
             if (x[v] >= thr) scratch[n++] = x[v];
-        qsort(scratch, (size_t)n, sizeof(double), cmp_desc);
-        double total = 0.0;
-        for (int32_t j = 0; j < n; ++j) total += exp(scratch[j] / temp - m);
+        if (n > 0 && m > -INFINITY) {
+            qsort(scratch, (size_t)n, sizeof(double), cmp_desc);
+            double total = 0.0;
+            for (int32_t j = 0; j < n; ++j) total += exp(scratch[j] / temp - m);
 
-        double cum = 0.0, prev_cum = 0.0;
-        int32_t j = 0;
-        double new_thr = scratch[n - 1];
-        while (j < n) {
-            double val = scratch[j];
-            double grp = 0.0;
-            while (j < n && scratch[j] == val) {
-                grp += exp(scratch[j] / temp - m);
-                ++j;
+            /* groups of equal logits, descending: value gval[g] (kept in place at
+             * the front of scratch), running mass gcum[g] up to and including it
+             * (e is free until the weights are written below) */
+            double *gval = scratch, *gcum = e;
+            int32_t ng = 0, j = 0;
+            double cum = 0.0;
+            while (j < n) {
+                double val = scratch[j];
+                double grp = 0.0;
+                while (j < n && scratch[j] == val) {
+                    grp += exp(scratch[j] / temp - m);
+                    ++j;
+                }
+                cum += grp / total;
+                gval[ng] = val;
+                gcum[ng] = cum;
+                ++ng;
             }
-            prev_cum = cum;
-            cum += grp / total;
-            if (cum >= top_p) { new_thr = val; break; }
+            /* the rule: first group at which the running mass reaches top_p */
+            int32_t close = ng - 1;
+            for (int32_t g = 0; g < ng; ++g)
+                if (gcum[g] >= top_p) { close = g; break; }
+            double a = fabs(gcum[close] - top_p);
+            double b = close > 0 ? fabs(gcum[close - 1] - top_p) : fabs(0.0 - top_p);
+            *nuc_margin = a < b ? a : b;
+            /* alternatives within the band */
+            for (int32_t g = close - 1; g >= 0 && gcum[g] >= top_p - nuc.band; --g)
+                ++*nuc_alt_lo;
+            for (int32_t g = close; g < ng - 1 && gcum[g] < top_p + nuc.band; ++g)
+                ++*nuc_alt_hi;
+            int32_t use = close + nuc.shift;
+            if (use < 0) use = 0;
+            if (use > ng - 1) use = ng - 1;
+            double new_thr = gval[use];
+            if (new_thr > thr) thr = new_thr;
         }
-        double a = fabs(cum - top_p), b = fabs(prev_cum - top_p);
-        *nuc_margin = a < b ? a : b;
-        if (new_thr > thr) thr = new_thr;
     }
 
     double m = -INFINITY;
@@ -198,7 +250,7 @@ static double kept_weights(const double *x, int32_t V, double temp,
     double S = 0.0;
     int32_t kept = 0;
     for (int32_t v = 0; v < V; ++v) {
-        if (x[v] >= thr) {
+        if (x[v] >= thr && m > -INFINITY) {
             e[v] = exp(x[v] / temp - m);
             if (e[v] > 0.0) ++kept;
         } else {
@@ -225,13 +277,28 @@ static double kept_weights(const double *x, int32_t V, double temp,
  * division sits between the exponentials and the decision.
  */
 static void step_row(const double *x, int32_t V, double c, double temp,
-                     int32_t top_k, double top_p,
+                     int32_t top_k, double top_p, ao_nucleus_opt nuc,
                      double *e, double *scratch, ao_step_result *out)
 {
-    int32_t n_kept;
+    int32_t n_kept, alt_lo, alt_hi;
     double nuc_margin;
-    double S = kept_weights(x, V, temp, top_k, top_p, e, scratch,
-                            &n_kept, &nuc_margin);
+    double S = kept_weights(x, V, temp, top_k, top_p, nuc, e, scratch,
+                            &n_kept, &nuc_margin, &alt_lo, &alt_hi);
+    out->nuc_margin = nuc_margin;
+    out->n_kept = n_kept;
+    out->nuc_alt_lo = alt_lo;
+    out->nuc_alt_hi = alt_hi;
+    out->tok_prev = -1; out->tok_next = -1;
+    out->p_prev = 0.0;  out->p_next = 0.0;
+    if (!(S > 0.0)) {
+        /* a row without any weight (no finite logit): nothing can be emitted.
+         * Defined sentinel: token -1, probability 0, the code unchanged. */
+        out->token = -1;
+        out->p = 0.0; out->f_lo = 0.0; out->f_hi = 0.0;
+        out->c_next = c;
+        out->delta = INFINITY;
+        return;
+    }
 
     double target = c * S;
     double run = 0.0, before = 0.0;
@@ -269,8 +336,13 @@ static void step_row(const double *x, int32_t V, double c, double temp,
         if (d2 < d) d = d2;
     }
     out->delta = fabs(d);
-    out->nuc_margin = nuc_margin;
-    out->n_kept = n_kept;
+
+    /* neighbours in the cumulative order: the tokens whose intervals touch
+     * the emitted one's (tokens of probability zero have empty intervals) */
+    for (int32_t v = tok - 1; v >= 0; --v)
+        if (e[v] > 0.0) { out->tok_prev = v; out->p_prev = e[v] / S; break; }
+    for (int32_t v = tok + 1; v < V; ++v)
+        if (e[v] > 0.0) { out->tok_next = v; out->p_next = e[v] / S; break; }
 }
 
 /*
@@ -280,6 +352,10 @@ static void step_row(const double *x, int32_t V, double c, double temp,
  * != 0) emit eos_id with probability one, keep their code and do not look at
  * their logits.  A row that emits eos_id is marked finished on output.
  * Every output pointer may be NULL.  nthreads <= 1 runs serially.
+ * nuc_shift / nuc_band: see ao_nucleus_opt (0, 0 for the rule itself);
+ * nuc_alt is [rows, 2] (admissible earlier, later closings), tok_nb and p_nb are
+ * [rows, 2] (previous, next token with non-zero probability; -1 / 0 if none).
+ * A row without any weight returns token -1, p = 0 and its code unchanged.
  * Returns 0, or -1 on an allocation failure.
  */
 int ao_step_rows(const void *logits, int dtype, int64_t rows, int64_t ld,
@@ -288,8 +364,11 @@ int ao_step_rows(const void *logits, int dtype, int64_t rows, int64_t ld,
                  const uint8_t *finished_in, int32_t eos_id,
                  int32_t *tokens, double *codes_next, double *p, double *f_lo,
                  double *f_hi, double *delta, double *nuc_margin,
-                 int32_t *n_kept, uint8_t *finished_out, int nthreads)
+                 int32_t *n_kept, uint8_t *finished_out, int nthreads,
+                 int32_t nuc_shift, double nuc_band, int32_t *nuc_alt,
+                 int32_t *tok_nb, double *p_nb)
 {
+    ao_nucleus_opt nuc = { nuc_shift, nuc_band };
     int failed = 0;
 #ifdef _OPENMP
     if (nthreads < 1) nthreads = 1;
@@ -316,12 +395,15 @@ int ao_step_rows(const void *logits, int dtype, int64_t rows, int64_t ld,
                 res.token = eos_id; res.p = 1.0; res.f_lo = 0.0; res.f_hi = 1.0;
                 res.c_next = codes[r]; res.delta = INFINITY;
                 res.nuc_margin = INFINITY; res.n_kept = 1;
+                res.nuc_alt_lo = 0; res.nuc_alt_hi = 0;
+                res.tok_prev = -1; res.tok_next = -1;
+                res.p_prev = 0.0; res.p_next = 0.0;
                 if (finished_out) finished_out[r] = 1;
             } else {
                 int64_t src = row_ids ? row_ids[r] : r;
                 for (int32_t v = 0; v < V; ++v)
                     x[v] = load_elem(logits, dtype, src * ld + v);
-                step_row(x, V, codes[r], temp, top_k, top_p, e, s, &res);
+                step_row(x, V, codes[r], temp, top_k, top_p, nuc, e, s, &res);
                 if (finished_out)
                     finished_out[r] = (eos_id >= 0 && res.token == eos_id) ? 1 : 0;
             }
@@ -333,6 +415,9 @@ int ao_step_rows(const void *logits, int dtype, int64_t rows, int64_t ld,
             if (delta)      delta[r] = res.delta;
             if (nuc_margin) nuc_margin[r] = res.nuc_margin;
             if (n_kept)     n_kept[r] = res.n_kept;
+            if (nuc_alt) { nuc_alt[2 * r] = res.nuc_alt_lo; nuc_alt[2 * r + 1] = res.nuc_alt_hi; }
+            if (tok_nb)  { tok_nb[2 * r] = res.tok_prev; tok_nb[2 * r + 1] = res.tok_next; }
+            if (p_nb)    { p_nb[2 * r] = res.p_prev; p_nb[2 * r + 1] = res.p_next; }
         }
         free(x); free(e); free(s);
     }
@@ -422,8 +507,17 @@ int ao_decode(const void *E, const void *U, int wdtype, int32_t V, int32_t d,
                 }
                 ao_bigram_logits(E, U, wdtype, V, d, scale, prev, round_mode, x);
                 ao_step_result res;
-                step_row(x, V, c, temp, top_k, top_p, e, s, &res);
+                const ao_nucleus_opt rule = { 0, 0.0 };
+                step_row(x, V, c, temp, top_k, top_p, rule, e, s, &res);
                 tokens[r * T + t] = res.token;
+                if (res.token < 0) {        /* a row without weight ends here */
+                    for (int32_t tt = t; tt < T; ++tt) {
+                        tokens[r * T + tt] = -1;
+                        if (p_out) p_out[r * T + tt] = 0.0;
+                        if (delta_out) delta_out[r * T + tt] = INFINITY;
+                    }
+                    break;
+                }
                 if (p_out) p_out[r * T + t] = res.p;
                 if (delta_out) delta_out[r * T + t] = res.delta;
                 c = res.c_next;
@@ -452,8 +546,11 @@ static void token_interval(const double *x, int32_t V, double temp,
                            int32_t top_k, double top_p, int32_t token,
                            double *e, double *s, double *f_lo, double *p)
 {
-    int32_t n_kept; double nm;
-    double S = kept_weights(x, V, temp, top_k, top_p, e, s, &n_kept, &nm);
+    int32_t n_kept, alo, ahi; double nm;
+    const ao_nucleus_opt rule = { 0, 0.0 };
+    double S = kept_weights(x, V, temp, top_k, top_p, rule, e, s, &n_kept, &nm,
+                            &alo, &ahi);
+    if (!(S > 0.0) || token < 0 || token >= V) { *f_lo = 0.0; *p = 0.0; return; }
     double before = 0.0;
     for (int32_t v = 0; v < token; ++v) before += e[v];
     *f_lo = before / S;

@@ -551,3 +551,123 @@ def test_code_at_interval_start_belongs_to_that_interval():
     x = np.array([[-np.inf, 0.0, -np.inf, 0.0, -np.inf]])
     r = oracle.step(x, np.array([0.0, 0.5, 0.999999]), row_ids=np.zeros(3, np.int64))
     assert r["token"].tolist() == [1, 3, 3]
+
+
+# --------------------------------------------------------------------------
+# what the checker needs beyond the rule itself: the neighbouring tokens of
+# the emitted one, the alternative closings of a nucleus whose running mass
+# passes within a band of top_p, and a defined answer for a row without weight
+# --------------------------------------------------------------------------
+def test_neighbours_are_the_adjacent_tokens_with_weight():
+    rng = np.random.default_rng(71)
+    R, V = 300, 40
+    x = rng.standard_normal((R, V)) * 2
+    x[rng.random((R, V)) < 0.4] = -np.inf                # empty intervals in between
+    x[:, 7] = 0.0                                        # every row keeps something
+    c = rng.random(R)
+    r = oracle.step(x, c)
+    for i in range(R):
+        p = softmax64(x[i])
+        live = np.nonzero(p > 0)[0]
+        pos = int(np.searchsorted(live, r["token"][i]))
+        assert live[pos] == r["token"][i]
+        want_prev = live[pos - 1] if pos > 0 else -1
+        want_next = live[pos + 1] if pos + 1 < len(live) else -1
+        assert r["tok_nb"][i].tolist() == [want_prev, want_next]
+        assert abs(r["p_nb"][i, 0] - (p[want_prev] if want_prev >= 0 else 0.0)) < 1e-15
+        assert abs(r["p_nb"][i, 1] - (p[want_next] if want_next >= 0 else 0.0)) < 1e-15
+        # the intervals touch: previous ends where this one starts, next starts where it ends
+        if want_prev >= 0:
+            assert abs(p[:want_prev + 1].sum() - r["f_lo"][i]) < 1e-12
+        if want_next >= 0:
+            assert abs(p[:want_next].sum() - r["f_hi"][i]) < 1e-12
+
+
+def _groups_desc(x, temp, keep):
+    p = np.zeros_like(x)
+    p[keep] = softmax64(x[keep], temp)
+    vals = np.unique(x[keep])[::-1]
+    cum = np.cumsum([p[keep & (x == v)].sum() for v in vals])
+    return vals, cum, p
+
+
+@pytest.mark.parametrize("top_k", [0, 12])
+def test_shifted_nucleus_closings_against_sorted_groups(top_k):
+    rng = np.random.default_rng(72)
+    R, V, temp, band = 150, 60, 0.9, 1e-5
+    stored = synth.f32_to_bf16_bits((rng.standard_normal((R, V)) * 2).astype(np.float32))
+    wide = synth.bf16_bits_to_f32(stored).astype(np.float64)
+    c = rng.random(R)
+    # put top_p a hair above or below a group end of each row in turn, so that alternatives exist
+    for trial, (which, eps) in enumerate([(1, 3e-6), (2, -4e-6), (3, 1e-9), (2, -1e-9), (1, 0.2)]):
+        for i in range(0, R, 7):
+            keep0 = topk_keep(wide[i], top_k)
+            vals, cum, _ = _groups_desc(wide[i], temp, keep0)
+            g = min(which, len(vals) - 2)
+            top_p = float(min(max(cum[g] + eps, 1e-3), 1 - 1e-3))
+            close = int(np.argmax(cum >= top_p)) if (cum >= top_p).any() else len(vals) - 1
+            n_lo = int(np.sum((cum[:close] >= top_p - band)))
+            n_hi = int(np.sum(cum[close:len(vals) - 1] < top_p + band))
+            # (the counts run contiguously from the rule's group because cum is increasing)
+            base = oracle.step(stored[i:i + 1], c[i:i + 1], temp=temp, top_k=top_k, top_p=top_p, band=band)
+            assert base["nuc_alt"][0].tolist() == [n_lo, n_hi], (trial, i)
+            shifts_seen = sorted(s for s, idx, sub in base["alt"])
+            assert shifts_seen == [s for s in range(-n_lo, n_hi + 1) if s != 0]
+            for shift in range(-2, 3):
+                r = oracle.step(stored[i:i + 1], c[i:i + 1], temp=temp, top_k=top_k, top_p=top_p,
+                                nuc_shift=shift)
+                use = min(max(close + shift, 0), len(vals) - 1)
+                keep = keep0 & (wide[i] >= vals[use])
+                assert r["n_kept"][0] == keep.sum(), (trial, i, shift)
+                p = np.zeros(V)
+                p[keep] = softmax64(wide[i][keep], temp)
+                F = np.cumsum(p)
+                tok = min(int(np.searchsorted(F, c[i], side="right")), int(np.nonzero(keep)[0][-1]))
+                lo = F[tok - 1] if tok > 0 else 0.0
+                if min(abs(c[i] - lo), abs(F[tok] - c[i])) < 1e-12:
+                    continue
+                assert r["token"][0] == tok and abs(r["p"][0] - p[tok]) < 1e-12
+                # and the alternatives handed out with the base call are these very results
+                for s, idx, sub in base["alt"]:
+                    if s == shift:
+                        assert sub["token"][0] == tok and abs(sub["p"][0] - p[tok]) < 1e-12
+
+
+def test_alternatives_follow_row_ids_and_finished_flags():
+    x = np.log(np.array([[0.5, 0.3, 0.15, 0.05], [0.4, 0.4, 0.1, 0.1]]))
+    codes = np.array([0.1, 0.7, 0.95, 0.2])
+    rid = np.array([0, 0, 1, 0])
+    fin = np.array([0, 0, 0, 1], np.uint8)
+    r = oracle.step(x, codes, top_p=0.8 + 2e-6, row_ids=rid, finished=fin, eos_id=3, band=1e-5)
+    # rows 0, 1 read logits row 0, whose mass 0.8 at the second group is a hair short of top_p: the rule keeps
+    # three tokens, one alternative keeps two; row 2 (0.8 after one group of two) likewise; row 3 is finished
+    assert r["n_kept"].tolist() == [3, 3, 4, 1]
+    assert r["nuc_alt"].tolist() == [[1, 0], [1, 0], [1, 0], [0, 0]]
+    (shift, idx, sub), = r["alt"]
+    assert shift == -1 and idx.tolist() == [0, 1, 2]
+    assert sub["n_kept"].tolist() == [2, 2, 2]
+    assert sub["token"].tolist() == [0, 1, 1]
+    assert np.allclose(sub["p"], [0.5 / 0.8, 0.3 / 0.8, 0.5])
+
+
+def test_row_without_weight_returns_the_sentinel():
+    x = np.full((3, 6), -np.inf)
+    x[1, 2] = np.nan
+    x[2, :] = np.nan
+    c = np.array([0.3, 0.6, 0.9])
+    for kw in (dict(), dict(top_k=2), dict(top_p=0.5), dict(top_k=3, top_p=0.9)):
+        r = oracle.step(x, c, **kw)
+        assert r["token"].tolist() == [-1, -1, -1]
+        assert np.all(r["p"] == 0.0) and np.array_equal(r["c_next"], c) and np.all(r["n_kept"] == 0)
+        f_lo, p = oracle.token_interval(x, np.array([0, 1, 2], np.int32), **kw)
+        assert np.all(p == 0.0)
+
+
+def test_nan_logits_are_never_kept_and_numbers_keep_their_order():
+    x = np.array([[np.nan, 1.0, np.nan, 3.0, 2.0, np.nan, 0.0]])
+    r = oracle.step(x, np.array([0.5]), top_k=2)
+    assert r["n_kept"][0] == 2 and r["token"][0] in (3, 4)
+    r = oracle.step(x, np.array([0.999]), top_k=6)          # fewer than k numbers: all of them stay
+    assert r["n_kept"][0] == 4 and r["token"][0] == 6
+    r = oracle.step(x, np.array([0.0]), top_p=0.6)          # 3.0 alone has mass 0.64
+    assert r["n_kept"][0] == 1 and r["token"][0] == 3
