@@ -140,6 +140,8 @@ def step(logits, codes, temp=1.0, top_k=0, top_p=1.0, finished=None,
     rid = None if row_ids is None else np.ascontiguousarray(row_ids, dtype=np.int64)
     fin = None if finished is None else np.ascontiguousarray(finished, dtype=np.uint8)
     out = _step_call(logits, dt, ld, V, codes, temp, top_k, top_p, fin, eos_id, rid, nthreads, nuc_shift, band)
+    call = dict(logits=logits, V=V, temp=temp, top_k=top_k, top_p=top_p, nthreads=nthreads)
+    out["_call"] = dict(call, row_ids=rid, finished=fin, nuc_shift=nuc_shift)
     out["alt"] = []
     if band > 0.0 and 0.0 < top_p < 1.0 and nuc_shift == 0:
         lo, hi = out["nuc_alt"][:, 0], out["nuc_alt"][:, 1]
@@ -151,8 +153,23 @@ def step(logits, codes, temp=1.0, top_k=0, top_p=1.0, finished=None,
             sub = _step_call(logits, dt, ld, V, np.ascontiguousarray(codes[idx]), temp, top_k, top_p,
                              None if fin is None else np.ascontiguousarray(fin[idx]), eos_id,
                              np.ascontiguousarray(src[idx]), nthreads, shift, band)
+            sub["_call"] = dict(call, row_ids=np.ascontiguousarray(src[idx]),
+                                finished=None if fin is None else np.ascontiguousarray(fin[idx]), nuc_shift=shift)
             out["alt"].append((shift, idx, sub))
     return out
+
+
+def interval_in(step_result, rows, tokens):
+    """(f_lo, p) of tokens[i] on row rows[i] of an earlier step() call (or of one of its alternatives), under the
+    same logits, modifiers and nucleus closing: where another token than the emitted one sits in that row's
+    cumulative distribution."""
+    c = step_result["_call"]
+    rows = np.asarray(rows, dtype=np.int64)
+    src = rows if c["row_ids"] is None else c["row_ids"][rows]
+    fin = None if c["finished"] is None else c["finished"][rows]
+    return token_interval(c["logits"], np.asarray(tokens, dtype=np.int32), temp=c["temp"], top_k=c["top_k"],
+                          top_p=c["top_p"], V=c["V"], finished=fin, row_ids=src, nthreads=c["nthreads"],
+                          nuc_shift=c["nuc_shift"])
 
 
 def bigram_logits(E, U, prev, scale=3.0, round_mode=0):
@@ -206,7 +223,7 @@ def estimate_mean(tokens, score, eos_id=-1):
 
 
 def token_interval(stored, tokens, temp=1.0, top_k=0, top_p=1.0, V=None,
-                   finished=None, row_ids=None, nthreads=1):
+                   finished=None, row_ids=None, nthreads=1, nuc_shift=0):
     """Per row: (f_lo, p) of tokens[r] in the row's kept, tempered softmax.
 
     `stored` as in `step`.  One step of the codebook recursion for a known
@@ -225,7 +242,7 @@ def token_interval(stored, tokens, temp=1.0, top_k=0, top_p=1.0, V=None,
                                       _ptr(rid), _ptr(tokens),
                                       float(temp), int(top_k), float(top_p),
                                       _ptr(fin),
-                                      _ptr(f_lo), _ptr(p), int(nthreads))
+                                      _ptr(f_lo), _ptr(p), int(nthreads), int(nuc_shift))
     if rc != 0:
         raise MemoryError("oracle token_interval failed")
     return f_lo, p

@@ -543,11 +543,12 @@ int ao_decode(const void *E, const void *U, int wdtype, int32_t V, int32_t d,
  * x holds the row's logits; e, s are scratch of V doubles.
  */
 static void token_interval(const double *x, int32_t V, double temp,
-                           int32_t top_k, double top_p, int32_t token,
+                           int32_t top_k, double top_p, int32_t nuc_shift,
+                           int32_t token,
                            double *e, double *s, double *f_lo, double *p)
 {
     int32_t n_kept, alo, ahi; double nm;
-    const ao_nucleus_opt rule = { 0, 0.0 };
+    const ao_nucleus_opt rule = { nuc_shift, 0.0 };
     double S = kept_weights(x, V, temp, top_k, top_p, rule, e, s, &n_kept, &nm,
                             &alo, &ahi);
     if (!(S > 0.0) || token < 0 || token >= V) { *f_lo = 0.0; *p = 0.0; return; }
@@ -561,13 +562,15 @@ static void token_interval(const double *x, int32_t V, double temp,
  * token_interval over rows of stored logits (layout and dtype as in
  * ao_step_rows): f_lo[r], p[r] for tokens[r].  Finished rows (already past
  * their EOS, Sec. 3.3) do not narrow the interval: f_lo = 0, p = 1.
+ * nuc_shift as in ao_nucleus_opt (0: the rule).
  * Returns 0, -1 on allocation failure.
  */
 int ao_token_interval_rows(const void *logits, int dtype, int64_t rows,
                            int64_t ld, int32_t V, const int64_t *row_ids,
                            const int32_t *tokens, double temp, int32_t top_k,
                            double top_p, const uint8_t *finished_in,
-                           double *f_lo, double *p, int nthreads)
+                           double *f_lo, double *p, int nthreads,
+                           int32_t nuc_shift)
 {
     int failed = 0;
 #ifdef _OPENMP
@@ -597,7 +600,7 @@ int ao_token_interval_rows(const void *logits, int dtype, int64_t rows,
             int64_t src = row_ids ? row_ids[r] : r;
             for (int32_t v = 0; v < V; ++v)
                 x[v] = load_elem(logits, dtype, src * ld + v);
-            token_interval(x, V, temp, top_k, top_p, tokens[r], e, s,
+            token_interval(x, V, temp, top_k, top_p, nuc_shift, tokens[r], e, s,
                            &f_lo[r], &p[r]);
         }
         free(x); free(e); free(s);
@@ -627,7 +630,7 @@ int ao_encode(const void *E, const void *U, int wdtype, int32_t V, int32_t d,
     for (int32_t t = 0; t < L; ++t) {
         ao_bigram_logits(E, U, wdtype, V, d, scale, prev, round_mode, x);
         double f_lo, p;
-        token_interval(x, V, temp, top_k, top_p, seq[t], e, s, &f_lo, &p);
+        token_interval(x, V, temp, top_k, top_p, 0, seq[t], e, s, &f_lo, &p);
         w += P * f_lo;
         P *= p;
         prev = seq[t];

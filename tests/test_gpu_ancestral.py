@@ -72,8 +72,13 @@ def test_ancestral_first_step_is_categorical_sampling():
     stored = from_dev_logits(logits)
     ref = oracle.step(stored, uni_h[0].astype(np.float64), temp=0.7, row_ids=np.zeros(N, np.int64), V=V, nthreads=8)
     got = tokens.cpu().numpy().reshape(N)
-    mism = got != ref["token"]
-    assert np.all(ref["delta"][mism] <= BAND), int(mism.sum())
+    # a draw next to an interval end may come out as another token, but only one whose own interval (as the
+    # oracle has it) lies within BAND of the draw
+    c = uni_h[0].astype(np.float64)
+    mism = np.nonzero(got != ref["token"])[0]
+    f_lo_g, p_g = oracle.interval_in(ref, mism, got[mism])
+    assert np.all((p_g > 0) & (c[mism] >= f_lo_g - BAND) & (c[mism] <= f_lo_g + p_g + BAND)), (mism, got[mism])
+    print(f"  {mism.size} of {N} draws come out as a token next to the oracle's", flush=True)
     # counts against N*p for the tokens that carry mass
     x = synth.bf16_bits_to_f32(stored[0]).astype(np.float64) / 0.7
     p = np.exp(x - x.max()); p /= p.sum()

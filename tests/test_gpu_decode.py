@@ -67,7 +67,7 @@ _GEMM_CASES = [
 
 
 @pytest.mark.parametrize("gm", [32, 4, 1])
-def test_bigram_logits_worker_placement(gm, monkeypatch):
+def test_bigram_logits_worker_placement(gm):
     """How the persistent kernel's workers are spread over the tiles changes which block computes a tile, not
     what the tile holds: every placement gives the default one's logits bit for bit."""
     import torch
@@ -77,9 +77,9 @@ def test_bigram_logits_worker_placement(gm, monkeypatch):
     prev = torch.from_numpy(np.random.default_rng(2).integers(0, V, R).astype(np.int32)).cuda()
     outs = []
     for knob in (None, gm):
-        if knob is not None:
-            monkeypatch.setenv("AS_GEMM_GM", str(knob))
         ctx = B.Ctx(R, V, torch.bfloat16)
+        if knob is not None:
+            ctx.set_tuning("gemm_gm", knob)
         out = torch.full((R, (V + 7) // 8 * 8), 7.0, dtype=torch.bfloat16, device="cuda")
         B.as_bigram_logits(ctx, model, prev, out)
         torch.cuda.synchronize()
@@ -89,15 +89,15 @@ def test_bigram_logits_worker_placement(gm, monkeypatch):
 
 
 @pytest.mark.parametrize("V,d,wdtype,ldtype,R,ldpad,knob", _GEMM_CASES)
-def test_bigram_logits_against_fp64(V, d, wdtype, ldtype, R, ldpad, knob, monkeypatch):
+def test_bigram_logits_against_fp64(V, d, wdtype, ldtype, R, ldpad, knob):
     import torch
     import oracle
     from paper_2210_15458_amd import binding as B
     from gpu_util import from_dev_logits
-    monkeypatch.setenv("AS_GEMM_SHAPE", str(knob))
     E, U, model = _upload_model(V, d, wdtype)
     tdt = torch.bfloat16 if ldtype == "bf16" else torch.float32
     ctx = B.Ctx(R, V, tdt)
+    ctx.set_tuning("gemm_shape", knob)
     prev = np.random.default_rng(1).integers(0, V, R).astype(np.int32)
     ld = (V + 7) // 8 * 8 + ldpad
     out = torch.full((R, ld), 7.0, dtype=tdt, device="cuda")
@@ -128,7 +128,7 @@ def _lockstep(cfg, B_, N, T, seed=0, check_steps=None, nthreads=8):
     import torch
     import oracle
     from paper_2210_15458_amd import binding as B
-    from gpu_util import compare_step, from_dev_logits
+    from gpu_util import BAND, compare_step, from_dev_logits
     V, d, temp, top_k, top_p, eos = cfg["V"], cfg["d"], cfg["temp"], cfg["top_k"], cfg["top_p"], cfg["eos_id"]
     tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
     E, U, model = _upload_model(V, d, cfg["dtype"], seed=seed)
@@ -147,7 +147,7 @@ def _lockstep(cfg, B_, N, T, seed=0, check_steps=None, nthreads=8):
     toks = torch.empty((R, T), dtype=torch.int32, device="cuda")
     tok_t = torch.empty(R, dtype=torch.int32, device="cuda")
     prob = torch.empty(R, dtype=torch.float32, device="cuda")
-    totals = dict(rows=0, mismatches=0, boundary=0, nucleus=0, in_band=0)
+    totals = dict(rows=0, mismatches=0, boundary=0, nucleus=0, nucleus_rows=0, in_band=0)
     for t in range(T):
         B.as_bigram_logits(ctx, model, prev, logits)
         torch.cuda.synchronize()
@@ -161,10 +161,12 @@ def _lockstep(cfg, B_, N, T, seed=0, check_steps=None, nthreads=8):
         if check_steps is None or t in check_steps:
             stored = from_dev_logits(logits)
             ref = oracle.step(stored, codes_in.astype(np.float64), temp=temp, top_k=top_k, top_p=top_p,
-                              finished=fin_in, eos_id=eos, V=V, nthreads=nthreads)
+                              finished=fin_in, eos_id=eos, V=V, nthreads=nthreads, band=BAND)
             gpu = dict(token=tok_t.cpu().numpy(), c_next=codes.cpu().numpy(), p=prob.cpu().numpy(),
                        finished=fin.cpu().numpy())
-            st = compare_step(gpu, ref, V, f"{cfg['name']} step {t}", trunc=(top_k > 0 or top_p < 1.0))
+            # (the model's rows are peaked: a nucleus that closes within the band of top_p is rare)
+            st = compare_step(gpu, ref, V, f"{cfg['name']} step {t}", trunc=(top_k > 0 or top_p < 1.0),
+                              codes=codes_in, eos_id=eos, max_alt_frac=0.02)
             for k in totals:
                 totals[k] += st[k]
             print(f"  step {t}: {st}", flush=True)
@@ -256,55 +258,215 @@ def test_decode_full_size_sampled_steps(cfg_id, trunc):
     assert totals["rows"] >= 3 * cfg["B"] * cfg["N"] // 2
 
 
-def test_wide_lattice_first_step_counts_and_monotonicity():
-    """One prompt, N = 65536 codes: the first step's row is shared by all codes,
-    so per-token counts must be floor/ceil of N*p (up to the fp32 rounding of the
-    codes) and tokens are non-decreasing in the lattice index (Sec. 4.3)."""
+def _free_running_oracle(ctx, model, prompts_h, N, T, codes0, V, tdt, temp, top_k, top_p, eos, nthreads=16):
+    """The oracle decoding on its own, with an fp64 code state, from the same start codes.  Its logits are the
+    rows the DEVICE stores for the conditioning tokens the oracle reaches (one row per distinct token, through
+    as_bigram_logits), so what parts the two trajectories is the code state and the per-element arithmetic, not
+    a differently rounded logit.  Returns tokens [R, T], p [R, T], delta [R, T]."""
     import torch
     import oracle
     from paper_2210_15458_amd import binding as B
     from gpu_util import from_dev_logits
+    R = codes0.shape[0]
+    codes = codes0.astype(np.float64)
+    prev = np.repeat(prompts_h.astype(np.int64), N)
+    fin = np.zeros(R, dtype=np.uint8)
+    toks = np.empty((R, T), dtype=np.int32)
+    ps = np.empty((R, T))
+    deltas = np.empty((R, T))
+    margins = np.empty((R, T))
+    ld = (V + 7) // 8 * 8
+    for t in range(T):
+        uniq, inv = np.unique(prev, return_inverse=True)
+        logits = torch.empty((len(uniq), ld), dtype=tdt, device="cuda")
+        B.as_bigram_logits(ctx, model, torch.from_numpy(uniq.astype(np.int32)).cuda(), logits)
+        torch.cuda.synchronize()
+        stored = from_dev_logits(logits)
+        del logits
+        ref = oracle.step(stored, codes, temp=temp, top_k=top_k, top_p=top_p, finished=fin, eos_id=eos,
+                          row_ids=inv.astype(np.int64), V=V, nthreads=nthreads)
+        toks[:, t], ps[:, t], deltas[:, t], margins[:, t] = ref["token"], ref["p"], ref["delta"], ref["nuc_margin"]
+        codes, fin, prev = ref["c_next"], ref["finished"], ref["token"].astype(np.int64)
+    return toks, ps, deltas, margins
+
+
+def _first_divergence_histogram(gpu_tokens, ref_tokens):
+    """How many codes first part from the reference at step t (index T: never within T steps)."""
+    T = gpu_tokens.shape[1]
+    diff = gpu_tokens != ref_tokens
+    first = np.where(diff.any(axis=1), diff.argmax(axis=1), T)
+    return np.bincount(first, minlength=T + 1)
+
+
+def _distinct_prefixes(tok):
+    """Number of distinct prefixes of every length 1..T among the rows of tok."""
+    out = []
+    for t in range(1, tok.shape[1] + 1):
+        out.append(len(np.unique(np.ascontiguousarray(tok[:, :t]), axis=0)))
+    return out
+
+
+def test_wide_lattice_full_shape():
+    """configs[4] at its own shape: one prompt, N = 65536 codes, T = 16 steps (Sec. 4.2 lattice, Sec. 4.3
+    duplicate bounds).
+      * every step, every row, lock-step against the oracle on the GPU's own inputs (the oracle is handed one
+        logits row per distinct conditioning token, after the device's rows for equal tokens have been shown
+        to be the same bits);
+      * as_decode equals that loop of exported calls;
+      * step 1, where all codes share one row: per-token counts are floor or ceil of N*p_v up to the fp32
+        rounding of the codes and the counted boundary rows, and equal the oracle's counts up to those rows;
+      * sequences are lexicographically non-decreasing in the lattice index (codes ascending, Sec. 4.3), so
+        the number of distinct prefixes is one more than the number of adjacent changes;
+      * the number of distinct prefixes of every length 1..T equals that of the oracle's tokens up to the rows
+        that differ (each boundary row moves a count by at most one);
+      * reported: the same counts and the first-divergence histogram against the oracle decoding on its own
+        with an fp64 code."""
+    import torch
+    import oracle
+    from paper_2210_15458_amd import binding as B
+    from gpu_util import BAND, compare_step, from_dev_logits
     cfg = synth.CONFIGS[4]
-    V, d, N, T = cfg["V"], cfg["d"], cfg["N"], 2
+    V, d, N, T, temp, eos = cfg["V"], cfg["d"], cfg["N"], cfg["T"], cfg["temp"], cfg["eos_id"]
     E, U, model = _upload_model(V, d, cfg["dtype"])
-    ctx = B.Ctx(N, V, torch.bfloat16)
-    prompts = synth.prompts(1, V, seed=1)
-    u = synth.shifts(1, seed=2)
-    out = torch.empty((1, N, T), dtype=torch.int32, device="cuda")
-    B.as_decode(ctx, model, torch.from_numpy(prompts).cuda(), N, T, torch.from_numpy(u).cuda(), cfg["temp"],
-                0, 1.0, cfg["eos_id"], out)
+    tdt = torch.bfloat16
+    ctx = B.Ctx(N, V, tdt)
+    prompts_h = synth.prompts(1, V, seed=1)
+    u_h = synth.shifts(1, seed=2)
+    pd, ud = torch.from_numpy(prompts_h).cuda(), torch.from_numpy(u_h).cuda()
+
+    codes = torch.empty(N, dtype=torch.float32, device="cuda")
+    B.as_lattice(ctx, ud, N, codes)
     torch.cuda.synchronize()
-    tok = out.cpu().numpy()[0]
-    first = tok[:, 0]
-    assert np.all(np.diff(first) >= 0), "tokens must be monotone in the code"
-    # the row every code saw at step 1, as the device stored it
-    row = torch.empty((1, (V + 7) // 8 * 8), dtype=torch.bfloat16, device="cuda")
-    B.as_bigram_logits(ctx, model, torch.from_numpy(prompts).cuda(), row)
+    codes0 = codes.cpu().numpy().copy()
+    assert np.all(np.diff(codes0) > 0)
+    prev = pd.repeat_interleave(N).contiguous()
+    fin = torch.zeros(N, dtype=torch.uint8, device="cuda")
+    ld = (V + 7) // 8 * 8
+    logits = torch.empty((N, ld), dtype=tdt, device="cuda")
+    tok_t = torch.empty(N, dtype=torch.int32, device="cuda")
+    prob = torch.empty(N, dtype=torch.float32, device="cuda")
+    G = np.empty((N, T), dtype=np.int32)            # the GPU's tokens
+    O = np.empty((N, T), dtype=np.int32)            # the oracle's, step by step on the GPU's inputs
+    differs = np.zeros(N, dtype=bool)
+    first_ref = None
+    for t in range(T):
+        B.as_bigram_logits(ctx, model, prev, logits)
+        prev_h = prev.cpu().numpy()
+        uniq, first_of, inv = np.unique(prev_h, return_index=True, return_inverse=True)
+        # rows of equal conditioning tokens hold the same bits: hand the oracle one row per distinct token
+        rows_u = logits[torch.from_numpy(first_of.astype(np.int64)).cuda()]
+        same = True
+        for lo in range(0, N, 8192):                 # (in slices: the gathered copy of all rows would be 4 GB)
+            idx = torch.from_numpy(inv[lo:lo + 8192].astype(np.int64)).cuda()
+            same = same and bool(torch.equal(logits[lo:lo + 8192].view(torch.int16), rows_u[idx].view(torch.int16)))
+        assert same, f"step {t}: rows with the same conditioning token differ"
+        stored = from_dev_logits(rows_u)
+        del rows_u
+        codes_in = codes.cpu().numpy().copy()
+        fin_in = fin.cpu().numpy().copy()
+        B.as_step_ex(ctx, logits, codes, temp, 0, 1.0, tok_t, codes, finished_in=fin, eos_id=eos, finished_out=fin,
+                     prob_out=prob)
+        torch.cuda.synchronize()
+        ref = oracle.step(stored, codes_in.astype(np.float64), temp=temp, finished=fin_in, eos_id=eos, V=V,
+                          row_ids=inv.astype(np.int64), nthreads=16)
+        gpu = dict(token=tok_t.cpu().numpy(), c_next=codes.cpu().numpy(), p=prob.cpu().numpy(),
+                   finished=fin.cpu().numpy())
+        st = compare_step(gpu, ref, V, f"wide lattice step {t}", codes=codes_in, eos_id=eos)
+        print(f"  step {t}: distinct conditioning tokens {len(uniq)}; {st}", flush=True)
+        G[:, t], O[:, t] = gpu["token"], ref["token"]
+        differs |= gpu["token"] != ref["token"]
+        if t == 0:
+            first_ref = ref
+        prev = tok_t.clone()
+
+    out = torch.full((1, N, T), -3, dtype=torch.int32, device="cuda")
+    B.as_decode(ctx, model, pd, N, T, ud, temp, 0, 1.0, eos, out)
     torch.cuda.synchronize()
-    stored = from_dev_logits(row)
-    codes = np.minimum(oracle.lattice(N, float(u[0])).astype(np.float32), np.float32(1 - 2.0 ** -24))
-    ref = oracle.step(stored, codes.astype(np.float64), V=V, row_ids=np.zeros(N, np.int64),
-                      temp=cfg["temp"], nthreads=16)
-    mism = first != ref["token"]
-    assert np.all(ref["delta"][mism] <= 1e-5)
-    print(f"  wide lattice: {mism.sum()} boundary-adjacent mismatches of {N}; "
-          f"{(ref['delta'] <= 1e-5).sum()} codes inside the band", flush=True)
+    assert np.array_equal(out.cpu().numpy()[0], G), "as_decode differs from the loop of exported calls"
+
+    # ---- step 1: counts
+    first = G[:, 0]
+    mism = int((first != first_ref["token"]).sum())
     cnt_g = np.bincount(first, minlength=V)
-    cnt_o = np.bincount(ref["token"], minlength=V)
-    assert np.abs(cnt_g - cnt_o).sum() <= 2 * mism.sum()
+    cnt_o = np.bincount(first_ref["token"], minlength=V)
+    assert np.abs(cnt_g - cnt_o).sum() <= 2 * mism
     p = np.zeros(V)
-    np.add.at(p, ref["token"], 0)                    # p from the oracle's own records:
-    p[ref["token"]] = ref["p"]
+    p[first_ref["token"]] = first_ref["p"]
     eps = 2 * N * 2.0 ** -24 + 1e-9                  # fp32 rounding of the codes moves a count by at most this
     seen = cnt_g > 0
-    assert np.all(cnt_g[seen] >= np.floor(N * p[seen] - eps) - mism.sum())
-    assert np.all(cnt_g[seen] <= np.ceil(N * p[seen] + eps) + mism.sum())
-    # distinct prefixes per length
+    assert np.all(cnt_g[seen] >= np.floor(N * p[seen] - eps) - mism)
+    assert np.all(cnt_g[seen] <= np.ceil(N * p[seen] + eps) + mism)
+    print(f"  step 1: {mism} boundary rows of {N}; {int(seen.sum())} distinct tokens", flush=True)
+
+    # ---- monotone sequences, distinct prefixes
     for t in range(1, T + 1):
-        distinct = len({tuple(r[:t]) for r in tok})
-        changes = 1 + int((np.any(tok[1:, :t] != tok[:-1, :t], axis=1)).sum())
-        print(f"  distinct prefixes of length {t}: {distinct} (adjacent changes + 1 = {changes})", flush=True)
-        assert distinct <= changes
+        a, b = G[:-1, :t], G[1:, :t]
+        neq = a != b
+        has = neq.any(axis=1)
+        k = neq.argmax(axis=1)
+        rows = np.nonzero(has)[0]
+        assert np.all(a[rows, k[rows]] < b[rows, k[rows]]), f"prefixes of length {t} are not non-decreasing"
+    dg, do = _distinct_prefixes(G), _distinct_prefixes(O)
+    changes = [1 + int(np.any(G[1:, :t] != G[:-1, :t], axis=1).sum()) for t in range(1, T + 1)]
+    nd = int(differs.sum())
+    print(f"  distinct prefixes, GPU:    {dg}\n  distinct prefixes, oracle: {do}\n  rows with a boundary "
+          f"mismatch at some step: {nd}", flush=True)
+    assert dg == changes
+    for t in range(T):
+        moved = int((G[:, :t + 1] != O[:, :t + 1]).any(axis=1).sum())
+        assert abs(dg[t] - do[t]) <= moved, (t + 1, dg[t], do[t], moved)
+
+    # ---- reported: the oracle on its own, fp64 code
+    F, Fp, Fd, _ = _free_running_oracle(ctx, model, prompts_h, N, T, codes0, V, tdt, temp, 0, 1.0, eos)
+    hist = _first_divergence_histogram(G, F)
+    df = _distinct_prefixes(F)
+    print(f"  free-running fp64 oracle: first divergence by step {hist.tolist()} (last entry: never)\n"
+          f"  distinct prefixes, free-running oracle: {df}", flush=True)
+    # the first step has the same inputs on both sides
+    assert hist[0] <= mism
+    assert abs(dg[0] - df[0]) <= mism
+    ctx.close()
+    model.close()
+
+
+@pytest.mark.parametrize("cfg_id,top_k,top_p", [(1, 0, 1.0), (2, 40, 1.0), (2, 0, 0.9)])
+def test_free_running_divergence_is_reported(cfg_id, top_k, top_p):
+    """How long the GPU's decode (fp32 code state, fp32 weights) stays on the trajectory of the oracle decoding
+    on its own with an fp64 code from the same start codes and the same stored logits: the histogram of the
+    first step at which they part, and how much of it the bits consumed so far explain (a code that has used
+    b bits of its 24 sits within 2^(b-24) of where the fp64 code sits, so it parts once an interval end comes
+    that close).  Required: every code whose path keeps farther than that (with a factor of 8) from every
+    interval end stays on the oracle's trajectory."""
+    import torch
+    import oracle
+    from paper_2210_15458_amd import binding as B
+    cfg = dict(synth.CONFIGS[cfg_id])
+    V, d, Bn, N, temp, eos = cfg["V"], cfg["d"], cfg["B"], cfg["N"], cfg["temp"], cfg["eos_id"]
+    T = min(cfg["T"], 24)
+    E, U, model = _upload_model(V, d, cfg["dtype"])
+    R = Bn * N
+    ctx = B.Ctx(R, V, torch.bfloat16)
+    prompts_h = synth.prompts(Bn, V, seed=1)
+    u_h = synth.shifts(Bn, seed=2)
+    codes = torch.empty(R, dtype=torch.float32, device="cuda")
+    B.as_lattice(ctx, torch.from_numpy(u_h).cuda(), N, codes)
+    out = torch.empty((Bn, N, T), dtype=torch.int32, device="cuda")
+    B.as_decode(ctx, model, torch.from_numpy(prompts_h).cuda(), N, T, torch.from_numpy(u_h).cuda(), temp, top_k, top_p,
+                eos, out)
+    torch.cuda.synchronize()
+    G = out.cpu().numpy().reshape(R, T)
+    F, Fp, Fd, Fm = _free_running_oracle(ctx, model, prompts_h, N, T, codes.cpu().numpy(), V, torch.bfloat16, temp,
+                                         top_k, top_p, eos)
+    hist = _first_divergence_histogram(G, F)
+    bits = np.concatenate([np.zeros((R, 1)), np.cumsum(-np.log2(Fp), axis=1)[:, :-1]], axis=1)   # used before step t
+    # (a nucleus that closes within 1e-5 of top_p may legitimately close elsewhere: such a step is not required)
+    safe = np.logical_and.accumulate((Fd > 1e-5 + 64.0 * 2.0 ** (bits - 24)) & (Fm > 1e-5), axis=1)
+    agree = G == F
+    assert np.all(agree[safe]), "a code far from every interval end left the oracle's trajectory"
+    med_bits = float(np.median(-np.log2(Fp[:, 0])))
+    print(f"  {cfg['name']} k={top_k} p={top_p}: first divergence from the free-running fp64 oracle by step "
+          f"{hist.tolist()} (last: none in {T} steps); median bits per step {med_bits:.2f}; "
+          f"{int(safe.sum())} (code, step) pairs required and equal", flush=True)
     ctx.close()
     model.close()
 

@@ -8,15 +8,17 @@ from paper_2210_15458_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def _check(V, R, dtype, temp=1.0, top_k=0, top_p=1.0, ld=None, sigma=3.0, seed=3, label=None, **kw):
+def _check(V, R, dtype, temp=1.0, top_k=0, top_p=1.0, ld=None, sigma=3.0, seed=3, label=None, tuning=None,
+           max_alt_frac=None, **kw):
     from gpu_util import compare_step, oracle_step, run_gpu_step
     stored = synth.gaussian_logits(R, V, sigma=sigma, seed=seed, dtype=dtype, ld=ld)
     codes = synth.uniform_codes(R, seed=seed + 1)
     label = label or f"V={V} R={R} {dtype} temp={temp} k={top_k} p={top_p} ld={ld}"
     print("case", label, flush=True)
-    gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, **kw)
+    gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, tuning=tuning, **kw)
     ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, **kw)
-    stats = compare_step(gpu, ref, V, label, trunc=(top_k > 0 or top_p < 1.0))
+    stats = compare_step(gpu, ref, V, label, trunc=(top_k > 0 or top_p < 1.0), codes=codes,
+                         eos_id=kw.get("eos_id", -1), max_alt_frac=max_alt_frac)
     print("   ", stats, flush=True)
     return gpu, ref, stats
 
@@ -61,7 +63,7 @@ def test_step_special_rows_and_codes():
         stored = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
         gpu = run_gpu_step(stored, codes, V)
         ref = oracle_step(stored, codes, V)
-        print(dtype, compare_step(gpu, ref, V, f"special {dtype}"), flush=True)
+        print(dtype, compare_step(gpu, ref, V, f"special {dtype}", codes=codes), flush=True)
         assert gpu["token"][0] == 1234 and gpu["token"][3] == V - 1 and gpu["token"][4] == 0
         assert gpu["token"][6] == ref["token"][6] and gpu["token"][7] == ref["token"][7]
 
@@ -79,7 +81,7 @@ def test_step_finished_rows_eos_and_row_ids():
     fin = (rng.random(R) < 0.3).astype(np.uint8)
     gpu = run_gpu_step(stored, codes, V, finished=fin, eos_id=1, row_ids=rid)
     ref = oracle_step(stored, codes, V, finished=fin, eos_id=1, row_ids=rid.astype(np.int64))
-    print(compare_step(gpu, ref, V, "finished/row_ids"), flush=True)
+    print(compare_step(gpu, ref, V, "finished/row_ids", codes=codes, eos_id=1), flush=True)
     assert np.all(gpu["token"][fin == 1] == 1)
     assert np.array_equal(gpu["c_next"][fin == 1], codes[fin == 1])       # code untouched
     assert np.all(gpu["finished"][fin == 1] == 1)
@@ -98,7 +100,7 @@ def test_step_row_ids_out_of_range_read_the_nearest_row(top_k, top_p):
     codes = synth.uniform_codes(rid.size, seed=32)
     gpu = run_gpu_step(stored, codes, V, top_k=top_k, top_p=top_p, row_ids=rid)
     ref = oracle_step(stored, codes, V, top_k=top_k, top_p=top_p, row_ids=np.clip(rid.astype(np.int64), 0, LR - 1))
-    print(compare_step(gpu, ref, V, "row_ids out of range", trunc=(top_k > 0 or top_p < 1.0)), flush=True)
+    print(compare_step(gpu, ref, V, "row_ids out of range", trunc=(top_k > 0 or top_p < 1.0), codes=codes), flush=True)
 
 
 @pytest.mark.parametrize("V,dtype,temp,top_k,top_p", [(32128, "bf16", 1.0, 40, 1.0), (32128, "bf16", 1.0, 0, 0.9),
@@ -117,7 +119,7 @@ def test_lattice_on_a_truncated_row_counts_and_monotonicity(V, dtype, temp, top_
     codes = np.minimum(oracle.lattice(N, 0.37).astype(np.float32), np.float32(1 - 2.0 ** -24))
     gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, row_ids=rid)
     ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, row_ids=rid.astype(np.int64))
-    stats = compare_step(gpu, ref, V, "lattice on a truncated row", trunc=True)
+    stats = compare_step(gpu, ref, V, "lattice on a truncated row", trunc=True, codes=codes)
     print("   ", stats, flush=True)
     tok = gpu["token"]
     assert np.all(np.diff(tok) >= 0)
@@ -167,11 +169,10 @@ def test_step_truncation(dtype, top_k, top_p, temp):
 
 
 @pytest.mark.parametrize("top_k,top_p", [(40, 1.0), (0, 0.9), (5, 0.5)])
-def test_step_truncation_radix_path(top_k, top_p, monkeypatch):
+def test_step_truncation_radix_path(top_k, top_p):
     # the general keep-threshold kernel on rows that would otherwise take the resident one
-    monkeypatch.setenv("AS_THR_PATH", "1")
-    _check(32128, 48, "bf16", top_k=top_k, top_p=top_p, seed=35)
-    _check(32128, 24, "f32", top_k=top_k, top_p=top_p, seed=36)
+    _check(32128, 48, "bf16", top_k=top_k, top_p=top_p, seed=35, tuning={"thr_path": 1})
+    _check(32128, 24, "f32", top_k=top_k, top_p=top_p, seed=36, tuning={"thr_path": 1})
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -198,7 +199,7 @@ def test_step_truncation_hard_rows(dtype):
         print("case", label, flush=True)
         gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p)
         ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p)
-        print("   ", compare_step(gpu, ref, V, label, trunc=True), flush=True)
+        print("   ", compare_step(gpu, ref, V, label, trunc=True, codes=codes), flush=True)
 
 
 @pytest.mark.parametrize("V,dtype", [(V, dt) for V in (7, 64, 255, 4097, 50257, 100003) for dt in ("bf16", "f32")
@@ -216,12 +217,11 @@ def test_step_shape_sweep(V, dtype):
                    sigma=float(rng.choice([0.5, 3.0, 8.0])), seed=int(rng.integers(1, 1 << 30)))
 
 
-def test_step_three_pass_kernel(monkeypatch):
+def test_step_three_pass_kernel():
     # the plain three-pass kernel, which no shape needs any more, forced by its knob
-    monkeypatch.setenv("AS_STEP_SHAPE", "9")
-    _check(1001, 24, "bf16", seed=41)
-    _check(4097, 12, "f32", temp=0.7, top_k=40, seed=42)
-    _check(32128, 8, "bf16", top_p=0.9, seed=43)
+    _check(1001, 24, "bf16", seed=41, tuning={"step_shape": 9})
+    _check(4097, 12, "f32", temp=0.7, top_k=40, seed=42, tuning={"step_shape": 9})
+    _check(32128, 8, "bf16", top_p=0.9, seed=43, tuning={"step_shape": 9})
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
