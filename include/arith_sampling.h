@@ -26,8 +26,12 @@
  *     lies in [0,V) and the new code in [0, 1 - 2^-24].
  *   - A logit of -inf is legal and means probability zero.
  *   - as_step / as_step_ex allocate nothing and touch only the context's
- *     fixed workspace.  as_decode and as_bigram_logits (re)allocate the
- *     context's decode workspace when a call needs more than any earlier one.
+ *     fixed workspace.  as_decode, as_decode_ancestral, as_decode_fused and
+ *     as_encode keep their logits and per-row state in a decode workspace that
+ *     the context (re)allocates when a call needs more than any earlier call
+ *     did: the first call at a size synchronises the stream, frees and
+ *     allocates, and must not be made under stream capture; later calls of the
+ *     same or a smaller size allocate nothing and can be captured.
  *   - One context must not be used from two host threads at once.
  */
 #ifndef ARITH_SAMPLING_H
@@ -75,6 +79,31 @@ as_status as_ctx_destroy(as_ctx *ctx);
 const char *as_last_error(const as_ctx *ctx);
 
 #define AS_MAX_VOCAB (1 << 21)
+
+/*
+ * Kernel choices, for tests and measurements (not part of the method; nothing
+ * in the environment changes what the library runs, only this call does).  Every
+ * knob starts at 0, the library's own choice; any setting gives the same results
+ * up to the tolerances stated for the call, only the kernel that computes them
+ * changes.  Takes effect for the calls that follow on this context.
+ *   AS_TUNE_STEP_SHAPE  work-group shape of the sampling kernel: 1..5 other
+ *                       (waves per row x KiB per wave) splits; 9 the plain
+ *                       three-pass kernel (slow; any alignment)
+ *   AS_TUNE_GEMM_SHAPE  logits kernel: 1 = the 128x256 tile kernel instead of
+ *                       the persistent one
+ *   AS_TUNE_THR_PATH    keep-threshold kernel: 1 = the radix select instead of
+ *                       the register-resident / streamed kernels
+ *   AS_TUNE_GEMM_GM     persistent logits kernel with more row tiles than
+ *                       workers: workers of one XCD along the rows (a divisor
+ *                       of the workers per XCD; otherwise ignored)
+ */
+typedef enum {
+    AS_TUNE_STEP_SHAPE = 0,
+    AS_TUNE_GEMM_SHAPE = 1,
+    AS_TUNE_THR_PATH = 2,
+    AS_TUNE_GEMM_GM = 3
+} as_tuning;
+as_status as_ctx_set_tuning(as_ctx *ctx, as_tuning knob, int32_t value);
 
 /*
  * Measurement aid (not part of the method): with profiling on, every launch of

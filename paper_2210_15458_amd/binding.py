@@ -52,6 +52,8 @@ def lib():
     L.as_decode_fused.argtypes = [vp, vp, vp, i32, i32, i32, vp, f32, i32, vp, vp]
     L.as_bigram_group_mass.argtypes = [vp, vp, vp, i64, f32, vp, i64]
     L.as_step_fused.argtypes = [vp, vp, vp, i64, vp, i64, vp, f32, vp, vp, vp, i32, vp]
+    L.as_ctx_set_tuning.argtypes = [vp, C.c_int, i32]
+    L.as_ctx_set_tuning.restype = C.c_int
     L.as_ctx_profile.argtypes = [vp, C.c_int]
     L.as_ctx_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(i64)]
     L.as_ctx_profile_samples.argtypes = [vp, C.c_int, C.POINTER(C.c_float), i64, C.POINTER(i64)]
@@ -109,6 +111,12 @@ class Ctx:
     def _check(self, rc):
         if rc != 0:
             raise ArithSamplingError(rc, (lib().as_last_error(self._h) or b"").decode())
+
+    TUNING = {"step_shape": 0, "gemm_shape": 1, "thr_path": 2, "gemm_gm": 3}
+
+    def set_tuning(self, knob, value):
+        """Pick a kernel variant (tests and measurements): knob is one of Ctx.TUNING."""
+        self._check(lib().as_ctx_set_tuning(self._h, self.TUNING[knob], int(value)))
 
     def profile(self, enable):
         self._check(lib().as_ctx_profile(self._h, 1 if enable else 0))

@@ -132,10 +132,6 @@ as_status as_ctx_create(as_ctx **out, int64_t max_rows, int32_t V, as_dtype logi
     c->max_rows = max_rows;
     c->V = V;
     c->dtype = logits_dtype;
-    if (const char *shape = getenv("AS_STEP_SHAPE")) c->step_shape = atoi(shape);
-    if (const char *shape = getenv("AS_GEMM_SHAPE")) c->gemm_shape = atoi(shape);
-    if (const char *path = getenv("AS_THR_PATH")) c->thr_path = atoi(path);
-    if (const char *gm = getenv("AS_GEMM_GM")) c->gemm_gm = atoi(gm);
     e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
     if (e != hipSuccess) {
         delete c;
@@ -171,6 +167,19 @@ as_status as_ctx_destroy(as_ctx *ctx)
 }
 
 const char *as_last_error(const as_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+as_status as_ctx_set_tuning(as_ctx *ctx, as_tuning knob, int32_t value)
+{
+    if (!ctx) return fail(nullptr, AS_ERR_INVALID_ARG, "ctx is NULL");
+    if (value < 0) return fail(ctx, AS_ERR_INVALID_ARG, "a tuning value is >= 0");
+    switch (knob) {
+    case AS_TUNE_STEP_SHAPE: ctx->step_shape = value; return AS_OK;
+    case AS_TUNE_GEMM_SHAPE: ctx->gemm_shape = value; return AS_OK;
+    case AS_TUNE_THR_PATH: ctx->thr_path = value; return AS_OK;
+    case AS_TUNE_GEMM_GM: ctx->gemm_gm = value; return AS_OK;
+    }
+    return fail(ctx, AS_ERR_INVALID_ARG, "unknown tuning knob");
+}
 
 as_status as_ctx_profile(as_ctx *ctx, int enable)
 {
