@@ -189,6 +189,32 @@ as_status as_step_ex(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld,
                      uint8_t *finished_out, float *prob_out, float *flo_out,
                      const int32_t *row_ids, int64_t logits_rows);
 
+/*
+ * as_step for callers that cannot allocate device memory and so cannot hold a
+ * context: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same kernels and same results as as_step; the per-row keep
+ * thresholds that the truncation kernels hand to the sampling kernel live in a
+ * fixed array inside the library's device image (AS_STATIC_MAX_ROWS floats,
+ * 256 KiB, held by every GPU the library runs on until the process ends).  The
+ * call allocates and frees nothing, on the device or through any library; the
+ * first call on a device looks the array's address up (no allocation).
+ *
+ *   logits_dtype, V   what a context would carry
+ *   rows              0 <= rows <= AS_STATIC_MAX_ROWS, else AS_ERR_INVALID_ARG
+ *   hip_stream        hipStream_t (as void*) of the current device; NULL = default
+ *   other arguments   as in as_step
+ * All calls on one GPU share the array: two calls whose kernels may overlap on
+ * that GPU (different streams, no ordering between them) race on it when
+ * top_k / top_p is on.  Nothing in it has to start at zero; every row's entry is
+ * written before it is read within one call.  Failures are reported through
+ * as_last_error(NULL).
+ */
+#define AS_STATIC_MAX_ROWS 65536
+as_status as_step_static(const void *logits, as_dtype logits_dtype, int64_t rows,
+                         int64_t ld, int32_t V, const float *codes, float temp,
+                         int32_t top_k, float top_p, int32_t *tokens_out,
+                         float *codes_out, void *hip_stream);
+
 /* ---------------------------------------------------------------- lattice */
 
 /*

@@ -40,6 +40,7 @@ def lib():
     L.as_last_error.restype = C.c_char_p
     L.as_step.argtypes = [vp, vp, i64, i64, vp, f32, i32, f32, vp, vp]
     L.as_step_ex.argtypes = [vp, vp, i64, i64, vp, f32, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, i64]
+    L.as_step_static.argtypes = [vp, C.c_int, i64, i64, i32, vp, f32, i32, f32, vp, vp, vp]
     L.as_lattice.argtypes = [vp, vp, i32, i32, vp]
     L.as_model_create_bigram.argtypes = [C.POINTER(vp), vp, vp, i32, i32, f32, C.c_int]
     L.as_model_destroy.argtypes = [vp]
@@ -60,7 +61,7 @@ def lib():
     L.as_ctx_profile_samples.restype = C.c_int
     L.as_ctx_profile.restype = C.c_int
     L.as_ctx_profile_read.restype = C.c_int
-    for name in ("as_ctx_create", "as_ctx_destroy", "as_step", "as_step_ex", "as_lattice",
+    for name in ("as_ctx_create", "as_ctx_destroy", "as_step", "as_step_ex", "as_step_static", "as_lattice",
                  "as_model_create_bigram", "as_model_destroy", "as_bigram_logits", "as_decode",
                  "as_interval_step", "as_encode", "as_decode_ancestral", "as_estimate_mean", "as_decode_fused",
                  "as_bigram_group_mass", "as_step_fused"):
@@ -189,6 +190,20 @@ def as_step(ctx, logits, codes, temp, top_k, top_p, tokens_out, codes_out):
     ctx._check(lib().as_step(ctx._h, ptr, rows, ld, _dev(codes, torch.float32, "codes", rows), float(temp),
                              int(top_k), float(top_p), _dev(tokens_out, torch.int32, "tokens_out", rows),
                              _dev(codes_out, torch.float32, "codes_out", rows)))
+
+
+def as_step_static(logits, V, codes, temp, top_k, top_p, tokens_out, codes_out, stream=None):
+    """as_step without a context (the entry point that allocates nothing); V columns of logits [rows, ld]."""
+    if logits.dim() != 2:
+        raise ValueError("logits must be [rows, ld]")
+    rows, ld = logits.shape
+    stream = torch.cuda.current_stream() if stream is None else stream
+    rc = lib().as_step_static(_dev(logits, logits.dtype, "logits"), _dtype_code(logits), rows, ld, int(V),
+                              _dev(codes, torch.float32, "codes", rows), float(temp), int(top_k), float(top_p),
+                              _dev(tokens_out, torch.int32, "tokens_out", rows),
+                              _dev(codes_out, torch.float32, "codes_out", rows), C.c_void_p(stream.cuda_stream))
+    if rc != 0:
+        raise ArithSamplingError(rc, (lib().as_last_error(None) or b"").decode())
 
 
 def as_step_ex(ctx, logits, codes, temp, top_k, top_p, tokens_out, codes_out, finished_in=None, eos_id=-1,

@@ -4,9 +4,17 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <mutex>
 #include <new>
 
 #include "as_common.hpp"
+
+// Workspace of as_step_static, the entry point for callers that cannot allocate: the per-row keep thresholds
+// that the threshold kernel hands to the sampling kernel.  Every GPU the library runs on holds its own copy
+// (256 KiB) until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// address the kernels are given is looked up once per device (static_scratch below).
+constexpr int64_t kStaticMaxRows = AS_STATIC_MAX_ROWS;
+static __device__ __align__(256) float scratch[kStaticMaxRows];
 
 namespace as {
 
@@ -83,6 +91,32 @@ static as_status row_ids_in_range(as_ctx *ctx, const int32_t *&row_ids, int64_t 
                        row_ids, ctx->rid, rows, top);
     AS_HIP_TRY(ctx, hipGetLastError());
     row_ids = ctx->rid;
+    return AS_OK;
+}
+
+// Device address of `scratch` on the current device, looked up on the first call made with that device current.
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static float *g_static_ptr[kMaxDevices] = {};
+
+static as_status static_scratch(int *device_out, float **ptr_out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, AS_ERR_UNSUPPORTED, "device ordinal beyond 63");
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return hip_fail(nullptr, e, "hipGetSymbolAddress(scratch)");
+        }
+        g_static_ptr[dev] = static_cast<float *>(p);
+    }
+    *device_out = dev;
+    *ptr_out = g_static_ptr[dev];
     return AS_OK;
 }
 
@@ -258,6 +292,48 @@ as_status as_step(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, con
 {
     return as_step_ex(ctx, logits, rows, ld, codes, temp, top_k, top_p, tokens_out, codes_out, nullptr, -1,
                       nullptr, nullptr, nullptr, nullptr, 0);
+}
+
+as_status as_step_static(const void *logits, as_dtype logits_dtype, int64_t rows, int64_t ld, int32_t V,
+                         const float *codes, float temp, int32_t top_k, float top_p, int32_t *tokens_out,
+                         float *codes_out, void *hip_stream)
+{
+    if (V < 1 || V > AS_MAX_VOCAB) return fail(nullptr, AS_ERR_INVALID_ARG, "V outside [1, AS_MAX_VOCAB]");
+    if (logits_dtype != AS_F32 && logits_dtype != AS_BF16)
+        return fail(nullptr, AS_ERR_INVALID_ARG, "unknown logits dtype");
+    if (rows < 0) return fail(nullptr, AS_ERR_INVALID_ARG, "rows is negative");
+    if (rows > kStaticMaxRows)
+        return fail(nullptr, AS_ERR_INVALID_ARG,
+                    "rows exceeds AS_STATIC_MAX_ROWS (65536), the size of the static workspace of as_step_static");
+    if (isnan(top_p)) return fail(nullptr, AS_ERR_INVALID_ARG, "top_p is NaN");
+    // a context that lives for this call only and owns nothing: its threshold workspace is the static array
+    as_ctx c;
+    as_status st = static_scratch(&c.device, &c.thr);
+    if (st != AS_OK) return st;
+    c.stream = static_cast<hipStream_t>(hip_stream);
+    c.max_rows = kStaticMaxRows;
+    c.V = V;
+    c.dtype = logits_dtype;
+    st = check_step(&c, logits, rows, ld, codes, temp, tokens_out, codes_out);
+    if (st == AS_OK && rows > 0) {
+        StepArgs a{};
+        a.logits = logits; a.rows = rows; a.ld = ld; a.V = V; a.dtype = logits_dtype;
+        a.codes = codes; a.temp = temp; a.k = 1.44269504088896340736f / temp; a.thr = nullptr;
+        a.tokens_out = tokens_out; a.tok_stride = 1; a.codes_out = codes_out;
+        a.finished_in = nullptr; a.eos_id = -1; a.finished_out = nullptr;
+        a.prob_out = nullptr; a.flo_out = nullptr; a.row_ids = nullptr; a.prev_out = nullptr;
+        bool done = false;
+        if (truncation_on(V, top_k, top_p)) {
+            done = launch_topk_step(&c, a, top_k, top_p, &st);
+            if (!done) {
+                st = launch_threshold(&c, logits, rows, ld, nullptr, nullptr, temp, top_k, top_p, c.thr);
+                a.thr = c.thr;
+            }
+        }
+        if (!done && st == AS_OK) st = launch_step(&c, a);
+    }
+    if (st != AS_OK) g_err = c.err;
+    return st;
 }
 
 as_status as_lattice(as_ctx *ctx, const float *u, int32_t B, int32_t N, float *codes_out)

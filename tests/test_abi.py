@@ -52,6 +52,9 @@ def test_host_side_argument_checks_need_no_gpu():
     assert rc == 1 and b"dtype" in lib.as_last_error(None)
     rc = lib.as_model_create_bigram(ctypes.byref(out), None, None, 16, 8, 3.0, 0)
     assert rc == 1
+    # the context-free step refuses more rows than its fixed workspace holds before it looks at a device
+    rc = lib.as_step_static(None, 0, 65537, 16, 16, None, 1.0, 0, 1.0, None, None, None)
+    assert rc == 1 and b"AS_STATIC_MAX_ROWS" in lib.as_last_error(None)
 
 
 def test_product_package_does_not_touch_the_oracle():
