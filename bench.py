@@ -21,8 +21,13 @@ Prints ONE JSON line: whole-job code-steps/s, plus
   logits_gemm   the MFMA logits kernel: achieved TFLOP/s against the bf16 peak
   cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on a bounded
                 sample of the same workload
+  other_configs compact legs for the other benchmark configurations at their full shapes
+                (configs[2] run twice, top-k=40 and top-p=0.9; configs[3]; configs[4]): whole-decode
+                code-steps/s, the sampling kernel's launch time and fraction of the HBM peak,
+                the logits kernel's launch time (skipped with --no-legs)
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -42,6 +47,102 @@ def spread(samples_ms):
     return {"median_us": float(q[0]), "p10_us": float(q[1]), "p90_us": float(q[2]), "launches": int(len(samples_ms))}
 
 
+def up(a):
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def sampling_kernel_name(V, ldt, top_k, top_p):
+    """Which kernel finishes the sampling step for this shape (the choice the library makes)."""
+    has_k, has_p = 0 < top_k < V, 0.0 < top_p < 1.0
+    if V <= 32768 and ((has_k and top_k <= 128) or (has_p and not has_k and ldt == "bf16")):
+        return ("threshold_resident_kernel with the sampling step fused (%s), as launched inside as_decode"
+                % ("top-k, candidates ranked in LDS" if has_k else "nucleus alone, row resident in registers"))
+    if has_k or has_p:
+        return "threshold kernel, then step_kernel (fused sampling step), as launched inside as_decode"
+    return "step_kernel (fused sampling step), as launched inside as_decode"
+
+
+def active_rows(tokens, eos):
+    """Rows still running at each decode step, averaged over the steps (finished rows are not read)."""
+    tk = tokens.cpu().numpy().reshape(-1, tokens.shape[-1])
+    T = tk.shape[1]
+    active = np.ones(tk.shape, dtype=bool)
+    for t in range(1, T):
+        active[:, t] = active[:, t - 1] & (tk[:, t - 1] != eos)
+    return float(active.sum()) / T
+
+
+def compact_leg(cfg_id, top_k, top_p, steps, warmup):
+    """One whole-decode measurement of another configuration at its full shape, with the kernels' own times."""
+    import torch
+    from paper_2210_15458_amd import binding as B
+    from paper_2210_15458_amd import synth
+    cfg = synth.CONFIGS[cfg_id]
+    V, d, Bn, N, T, temp, eos = cfg["V"], cfg["d"], cfg["B"], cfg["N"], cfg["T"], cfg["temp"], cfg["eos_id"]
+    R = Bn * N
+    E, U = synth.bigram_weights(V, d, seed=0, dtype=cfg["dtype"])
+    Ed, Ud = up(E), up(U)
+    del E, U
+    model = B.Model(Ed, Ud, scale=cfg["scale"])
+    del Ud
+    prompts, u = up(synth.prompts(Bn, V, seed=1)), up(synth.shifts(Bn, seed=2))
+    ctx = B.Ctx(R, V, torch.bfloat16)
+    tokens = torch.empty((Bn, N, T), dtype=torch.int32, device="cuda")
+    for _ in range(warmup):
+        B.as_decode(ctx, model, prompts, N, T, u, temp, top_k, top_p, eos, tokens)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.as_decode(ctx, model, prompts, N, T, u, temp, top_k, top_p, eos, tokens)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx.profile(True)
+    for _ in range(steps):
+        B.as_decode(ctx, model, prompts, N, T, u, temp, top_k, top_p, eos, tokens)
+    torch.cuda.synchronize()
+    step_samples, gemm_samples, thr_samples = ctx.profile_samples(0), ctx.profile_samples(1), ctx.profile_samples(2)
+    ctx.profile_read(0); ctx.profile_read(1); ctx.profile_read(2)
+    ctx.profile(False)
+    act = active_rows(tokens, eos)
+    bytes_per_row = V * 2 + 18
+    # the sampling step of a launch: the kernel that finishes it, plus the threshold kernel where that is separate
+    samp_us = float(np.mean(step_samples)) * 1e3 + (float(np.mean(thr_samples)) * 1e3 if len(thr_samples) else 0.0)
+    ach = act * bytes_per_row / (samp_us * 1e-6) / 1e9
+    out = {
+        "workload": f"configs[{cfg_id}] {cfg['name']}: as_decode V={V} d={d} bf16, B={Bn} N={N} (R={R}) T={T} "
+                    f"temp={temp} top_k={top_k} top_p={top_p} eos={eos}",
+        "value": R * T * steps / (t1 - t0), "unit": "code-steps/s", "decodes_timed": steps,
+        "ms_per_decode": (t1 - t0) / steps * 1e3,
+        "sampling": {"kernel": sampling_kernel_name(V, "bf16", top_k, top_p), "bound": "hbm",
+                     "avg_launch_us": samp_us, "spread": spread(step_samples), "achieved": ach, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "bytes_per_code_step": bytes_per_row,
+                     "active_rows_per_launch": act},
+        "logits_gemm": {"avg_launch_us": float(np.mean(gemm_samples)) * 1e3, "spread": spread(gemm_samples),
+                        "achieved": 2.0 * R * d * V / (float(np.mean(gemm_samples)) * 1e-3) / 1e12,
+                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}}
+    out["logits_gemm"]["frac"] = out["logits_gemm"]["achieved"] / MFMA_BF16_PEAK_TFLOPS
+    if len(thr_samples):
+        out["sampling"]["threshold_kernel_us"] = float(np.mean(thr_samples)) * 1e3
+    ctx.close()
+    model.close()
+    del Ed, tokens
+    torch.cuda.empty_cache()
+    return out
+
+
+def source_stamp():
+    """Hash of the sources the sampling kernel is built from (ties a stored counter reading to the kernel timed)."""
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2210_15458_amd", "csrc")
+    h = hashlib.sha256()
+    for name in ("as_step.hip", "as_row.hpp", "as_common.hpp"):
+        with open(os.path.join(here, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +155,10 @@ def main():
                     help="storage type of the logits between the two kernels (default: the configuration's)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold (rotating buffers) kernel leg")
+    ap.add_argument("--no-legs", action="store_true", help="skip the compact legs for the other configurations")
+    ap.add_argument("--only-leg", default=None,
+                    help="run nothing but one compact leg (configs2_topk, configs2_nucleus, configs3, configs4) "
+                         "and print it: for kernel traces and counter runs of that configuration")
     ap.add_argument("--rows16x", action="store_true",
                     help="add the leg that runs the sampling kernel once over 16x the rows (its launches carry the "
                          "same kernel name, so a kernel trace of a run with this flag averages over both sizes)")
@@ -70,6 +175,13 @@ def main():
     from paper_2210_15458_amd import binding as B
     from paper_2210_15458_amd import synth
 
+    legs = {"configs2_topk": (2, 40, 1.0, 3), "configs2_nucleus": (2, 0, 0.9, 3), "configs3": (3, 0, 1.0, 2),
+            "configs4": (4, 0, 1.0, 2)}
+    if args.only_leg:
+        cid, k_, p_, n_ = legs[args.only_leg]
+        print(json.dumps({args.only_leg: compact_leg(cid, k_, p_, n_, 1)}))
+        return 0
+
     cfg = synth.CONFIGS[args.config]
     V, d, Bn, N, T = cfg["V"], cfg["d"], cfg["B"], cfg["N"], cfg["T"]
     temp, top_k, top_p, eos = cfg["temp"], cfg["top_k"], cfg["top_p"], cfg["eos_id"]
@@ -81,11 +193,6 @@ def main():
     ldt = args.logits or cfg["dtype"]
     tdt = torch.bfloat16 if ldt == "bf16" else torch.float32
     esz = 2 if ldt == "bf16" else 4
-
-    def up(a):
-        if a.dtype == np.uint16:
-            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-        return torch.from_numpy(a).cuda()
 
     E, U = synth.bigram_weights(V, d, seed=0, dtype=cfg["dtype"])
     Ed, Ud = up(E), up(U)
@@ -127,11 +234,7 @@ def main():
     wall = t1 - t0
     code_steps = R * T * args.steps
     # rows that were still running, per launch: finished rows are not read
-    tk = tokens.cpu().numpy().reshape(R, T)
-    active = np.ones((R, T), dtype=bool)
-    for t in range(1, T):
-        active[:, t] = active[:, t - 1] & (tk[:, t - 1] != eos)
-    active_rows_per_launch = float(active.sum()) / T
+    active_rows_per_launch = active_rows(tokens, eos)
     bytes_per_row = V * esz + 18           # the logits row + code in/out, token, flags
     step_avg_us = step_ms / max(step_n, 1) * 1e3
     achieved = active_rows_per_launch * bytes_per_row / (step_avg_us * 1e-6) / 1e9 if step_n else None
@@ -155,9 +258,7 @@ def main():
                    "storage": ldt, "rows": R, "decode_steps": T,
                    "value_with_dispatch_events": code_steps / (t3 - t2)},
         "roofline": {
-            "kernel": ("threshold_resident_kernel with the sampling step fused (top-k rows), as launched inside "
-                       "as_decode" if 0 < top_k <= 128 else
-                       "step_kernel (fused sampling step), as launched inside as_decode"),
+            "kernel": sampling_kernel_name(V, ldt, top_k, top_p),
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
             "avg_launch_us": step_avg_us, "launches": step_n, "untimed_launches": step_drop,
@@ -270,11 +371,16 @@ def main():
 
     # ---- measured HBM traffic of the sampling kernel, if a counter run has been recorded
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "step_kernel_traffic.json")
-    if os.path.exists(traffic_file) and args.config == 1:
+    if os.path.exists(traffic_file) and args.config == 1 and top_k <= 0 and not (0.0 < top_p < 1.0) and ldt == "bf16":
         with open(traffic_file) as f:
             tr = json.load(f)
-        out["roofline"]["traffic"] = tr.get("traffic_bytes_per_launch")
-        out["roofline"]["traffic_source"] = tr.get("source")
+        # a counter reading of another build of the kernel says nothing about the one timed here
+        if tr.get("source_stamp") == source_stamp():
+            out["roofline"]["traffic"] = tr.get("traffic_bytes_per_launch")
+            out["roofline"]["traffic_source"] = tr.get("source")
+        else:
+            out["roofline"]["traffic_source"] = ("no counter reading of this build of the kernel is stored "
+                                                 "(profiles/step_kernel_traffic.json is of another one)")
 
     # ---- cold leg: the sampling kernel alone, rotating over > 1 GiB of logits
     if not args.no_cold:
@@ -382,9 +488,18 @@ def main():
                       f"{reps} repetitions, {nthreads} OpenMP threads, {c1 - c0:.2f} s wall; sampling step "
                       f"only (the oracle's fp64 logits GEMM is not included)"}
 
-    print(json.dumps(out))
     ctx.close()
     model.close()
+    del Ed, tokens
+    torch.cuda.empty_cache()
+
+    # ---- the other configurations at their full shapes, compactly
+    if not args.no_legs and args.config == 1:
+        out["other_configs"] = {}
+        for name, (cid, k_, p_, n_) in legs.items():
+            out["other_configs"][name] = compact_leg(cid, k_, p_, n_, 1)
+
+    print(json.dumps(out))
     return 0
 
 
