@@ -87,8 +87,9 @@ const char *as_last_error(const as_ctx *ctx);
  * up to the tolerances stated for the call, only the kernel that computes them
  * changes.  Takes effect for the calls that follow on this context.
  *   AS_TUNE_STEP_SHAPE  work-group shape of the sampling kernel: 1..5 other
- *                       (waves per row x KiB per wave) splits; 9 the plain
- *                       three-pass kernel (slow; any alignment)
+ *                       (waves per row x KiB per wave) splits; 6 the general
+ *                       kernel also for rows that fit the single-tile one;
+ *                       9 the plain three-pass kernel (slow; any alignment)
  *   AS_TUNE_GEMM_SHAPE  logits kernel: 1 = the 128x256 tile kernel instead of
  *                       the persistent one
  *   AS_TUNE_THR_PATH    keep-threshold kernel: 1 = the radix select instead of

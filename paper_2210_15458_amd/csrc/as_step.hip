@@ -37,7 +37,10 @@
 //     still in registers when the row is a single tile; otherwise the share is
 //     read again.
 //   * Rows that do not start on 16 bytes or whose length is not a whole number
-//     of vectors take a plain three-pass kernel (step_generic_kernel).
+//     of vectors take the same kernel in a form that masks the row's two ends
+//     (PARTIAL); rows of whole vectors that fit one tile take step_tile_kernel
+//     further down.  The plain three-pass kernel (step_generic_kernel) is left
+//     behind its knob.
 #include <type_traits>
 #include <utility>
 
@@ -506,6 +509,258 @@ __global__ __launch_bounds__(NW * 64, OCC) void step_kernel(StepArgs a, int ntil
 }
 
 // ===========================================================================
+// single-tile kernel: a row of whole, aligned vectors that fits one tile (4 waves x 16 KiB: 32768 bf16 or
+// 16384 fp32 logits), the shape of the headline workload.  Same sums in the same vocabulary order as
+// step_kernel, with what a one-tile row allows.
+//
+// What the clock says about this shape (1024 rows, every block resident at once): a CU's memory pipeline takes
+// the 256 loads of its 16 waves at the rate the data comes back, so a wave spends most of its life waiting to
+// issue its loads, cannot work on anything meanwhile, and has its data almost as soon as its last load is
+// accepted.  The launch therefore takes the time of a read-only kernel of the same shape plus whatever a wave
+// still has to do after its last chunk has landed, and the design minimises that remainder:
+//   * one integer reference per WAVE, taken from the share's first chunk (or from the keep threshold): every
+//     later chunk is unpack, fma, exp2, add and nothing else, worked on as it lands, with no maximum and no
+//     change of reference.  Weights may exceed 1 (the reference is not the share's maximum); a share whose
+//     weights overflow fp32 (a logit more than 127/k above the first chunk's largest) makes the sums non-finite,
+//     which the block sees after its barrier and answers with the plain three-pass routine.
+//   * the sums of the 64 chunks of the row (one wave reduction per chunk, four at a time, done while later
+//     chunks are still on their way) go to LDS; after the one barrier a single fp64 scan over those 64 values
+//     gives the total, the target c*S and the chunk that holds it - share, group and chunk in one step.
+//   * the wave that owns that chunk has the lane sums of its chunks in registers: one more scan finds the lane,
+//     and that lane the element.
+// ===========================================================================
+// Four independent wave sums at once: the DPP steps of the four interleave, which hides their latency and makes
+// the wait states between dependent DPP instructions free.  The totals are left in lane 63.
+__device__ __forceinline__ void wave_sum4_in_lane63(float &a, float &b, float &c, float &d)
+{
+#define AS_DPP4(ctrl)                                                 \
+    "v_add_f32_dpp %0, %0, %0 " ctrl " bank_mask:0xf\n\t"           \
+    "v_add_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t"           \
+    "v_add_f32_dpp %2, %2, %2 " ctrl " bank_mask:0xf\n\t"           \
+    "v_add_f32_dpp %3, %3, %3 " ctrl " bank_mask:0xf\n\t"
+    asm volatile("s_nop 1\n\t"
+                 AS_DPP4("row_shr:1 row_mask:0xf")
+                 AS_DPP4("row_shr:2 row_mask:0xf")
+                 AS_DPP4("row_shr:4 row_mask:0xf")
+                 AS_DPP4("row_shr:8 row_mask:0xf")
+                 AS_DPP4("row_bcast:15 row_mask:0xa")
+                 AS_DPP4("row_bcast:31 row_mask:0xc")
+                 "s_nop 0"
+                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+#undef AS_DPP4
+}
+
+template <int DT, bool HAS_THR>
+__global__ __launch_bounds__(256, 4) void step_tile_kernel(StepArgs a)
+{
+    using T = typename Elem<DT>::T;
+    constexpr int EPV = Elem<DT>::kPerVec;
+    // (eight waves of 8 KiB per row, which this code also fits in 64 registers, measured the same)
+    constexpr int NW = 4, ITERS = 64 / NW, G = 4, NG = ITERS / G;
+    constexpr int kShare = ITERS * 64;                // vectors per share
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+    __shared__ __attribute__((aligned(16))) float chunk_sum[NW * ITERS];   // sum of every chunk of the row, vocabulary order
+    __shared__ __attribute__((aligned(16))) float share_ref[NW];           // the integer reference its share's sums are relative to
+    __shared__ GenericScratch gen;
+
+    const int64_t r = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    // What is known per row sits at wave-uniform addresses: scalar loads, requested before anything else and
+    // looked at only after the first vector loads are on their way.  The finished flag, one byte, comes as the
+    // aligned 32-bit word that holds it (there are no scalar byte loads).
+    uint32_t fin_word = 0u, fin_at = 0u;
+    if (a.finished_in != nullptr) {
+        const uint8_t *q = a.finished_in + r;
+        fin_at = (uint32_t)(reinterpret_cast<uintptr_t>(q) & 3u);
+        fin_word = *reinterpret_cast<const uint32_t *>(q - fin_at);
+    }
+    const float code = a.codes[r];
+    float thr = -__builtin_inff();
+    if constexpr (HAS_THR) thr = a.thr[r];
+    const int64_t src = a.row_ids ? (int64_t)a.row_ids[r] : r;
+    const unsigned char *rowb =
+        reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.logits) + src * a.ld);
+    const int32_t nvec = a.V / EPV;
+    const float k = a.k;
+
+    const int32_t v0 = wave * kShare;
+    u32x4 raw[ITERS];
+    float rw = kRefFloor;
+    // chunks of the share in which this lane is inside the row (a lane past the row's end re-reads its last
+    // real vector, or the share's first one, and its sums are zeroed)
+    int32_t mych = (nvec - v0 - lane + 63) >> 6;
+    mych = mych < 0 ? 0 : (mych > ITERS ? ITERS : mych);
+    const bool live = v0 < nvec;                         // wave-uniform: the share holds some of the row
+    const bool ragged = v0 + kShare > nvec;              // wave-uniform: ... and not all of its chunks are whole
+    // the lane's sum over one chunk, relative to rw (nr = -rw)
+    auto lane_sum = [&](const u32x4 &v, float nr) __attribute__((always_inline)) {
+        float x[EPV], e[EPV];
+        unpack<DT>(v, x);
+#pragma unroll
+        for (int i = 0; i < EPV; ++i) {
+            e[i] = fast_exp2(fmaf(x[i], k, nr));
+            if constexpr (HAS_THR) e[i] = (x[i] >= thr) ? e[i] : 0.f;
+        }
+        return vec_sum<EPV>(e);
+    };
+    const unsigned char *base = rowb + (size_t)(live ? v0 : 0) * 16u;
+    const uint32_t off0 = (uint32_t)lane * 16u;
+    const uint32_t off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
+    // Every offset is clamped to the lane's last vector inside the row (only the one share of a row that runs
+    // past its end needs it).  The two vector instructions this puts between consecutive loads are not a cost:
+    // with addresses that need none (a scalar base per group and immediates) the launch is 0.8 us slower; a wave
+    // that issues its loads back to back takes the CU's memory pipeline for itself, the four waves of a row
+    // drift apart and wait for each other at the barrier.
+    auto request_group = [&](int g) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jj = 0; jj < G; ++jj) {
+            uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+            off = off < off_last ? off : off_last;
+            // streamed once: non-temporal, so the row does not push other data out of L2
+            raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+        }
+    };
+    // The first group is requested before the row's finished flag is looked at: the flag is a memory round trip
+    // of its own, and the row's first bytes need not wait behind it.  (A finished row thus costs a few KiB
+    // of its logits; an unfinished one starts earlier.)
+    if (live) request_group(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (((fin_word >> (8u * fin_at)) & 0xffu) != 0u) {
+        if (threadIdx.x == 0) write_finished(a, r);
+        return;
+    }
+    f32x4 *const my_sums = reinterpret_cast<f32x4 *>(chunk_sum + wave * ITERS);
+    auto stream = [&](auto ragged_c) __attribute__((always_inline)) {
+        constexpr bool RAGGED = decltype(ragged_c)::value;
+#pragma unroll
+        for (int g = 1; g < NG; ++g) request_group(g);
+        // keep the requests in vocabulary order and where they are written: the consumer waits for them one
+        // by one, in this order
+        __builtin_amdgcn_sched_barrier(0);
+        // the wave's reference: from the first chunk's largest kept logit and, with a threshold, the threshold
+        // itself (every kept logit is at or above it)
+        {
+            float x[EPV];
+            unpack<DT>(raw[0], x);
+            if constexpr (HAS_THR) {
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) x[i] = (x[i] >= thr) ? x[i] : -__builtin_inff();
+            }
+            float m = vec_max<EPV>(x);
+            if constexpr (RAGGED) m = mych > 0 ? m : -__builtin_inff();
+            m = wave_max(m);
+            if constexpr (HAS_THR) m = fmaxf(m, thr);
+            rw = fmaxf(ceilf(m * k), kRefFloor);
+        }
+        const float nr = -rw;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            float t[G];
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                const int j = g * G + jj;
+                t[jj] = lane_sum(raw[j], nr);
+                if constexpr (RAGGED) t[jj] = j < mych ? t[jj] : 0.f;
+            }
+            // the group's four chunk sums over the wave, to LDS by the lane that ends up with them
+            wave_sum4_in_lane63(t[0], t[1], t[2], t[3]);
+            if (lane == 63) my_sums[g] = f32x4{t[0], t[1], t[2], t[3]};
+        }
+    };
+    if (live) {
+        if (!ragged) stream(std::false_type{});
+        else stream(std::true_type{});
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITERS; ++j) raw[j] = u32x4{0u, 0u, 0u, 0u};
+        if (lane < NG) my_sums[lane] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (lane == 0) share_ref[wave] = rw;
+    __syncthreads();
+
+    // ---------------- every wave: one scan over the row's 64 chunk sums (fp64): total, target, owning chunk
+    float R = share_ref[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) R = fmaxf(R, share_ref[w]);
+    const float my_ref = share_ref[lane / ITERS];
+    const double cv = (double)ldexpf(chunk_sum[lane], shift_of(my_ref, R));
+    const double cincl = wave_scan_add(cv);
+    const double S = read_lane(cincl, 63);
+    if (!(S < (double)__builtin_inff())) {
+        // weights beyond fp32 against a first-chunk reference, or NaN in the data: the plain routine
+        generic_step_row<T>(a, r, thr, gen);
+        return;
+    }
+    const double tau = (double)code * S;
+    const unsigned long long chit = __ballot(cincl > tau);
+    const unsigned long long cnz = __ballot(cv > 0.0);
+    // the first chunk whose running sum passes c*S; past the end by rounding: the last chunk that holds weight
+    const int ch = chit ? (__ffsll((long long)chit) - 1) : (cnz ? (63 - __clzll((long long)cnz)) : 0);
+    if (wave != ch / ITERS) return;
+    const double run = read_lane(cincl - cv, ch);
+
+    // ---------------- owning wave: lane, then element.  Everything it holds is relative to rw.
+    const int shf = shift_of(rw, R);
+    const int cj = ch % ITERS;
+    u32x4 hv;
+    with_uniform_index<0, ITERS>(cj, [&](auto c_c) __attribute__((always_inline)) {
+        uint32_t w0 = raw[decltype(c_c)::value][0], w1 = raw[decltype(c_c)::value][1],
+                 w2 = raw[decltype(c_c)::value][2], w3 = raw[decltype(c_c)::value][3];
+        // opaque to the optimiser: keeps this a tree of branches over registers instead of an indexed read
+        // that would force the array into memory
+        asm volatile("" : "+v"(w0), "+v"(w1), "+v"(w2), "+v"(w3));
+        hv = u32x4{w0, w1, w2, w3};
+    });
+    // the lane sums of that chunk once more (sixteen sums per lane kept for this would cost the registers
+    // that let a row have eight waves)
+    float cl = lane_sum(hv, -rw);
+    if (ragged) cl = cj < mych ? cl : 0.f;
+    const double lv = (double)ldexpf(cl, shf);
+    const double incl2 = wave_scan_add(lv) + run;
+    const unsigned long long hit2 = __ballot(incl2 > tau);
+    const unsigned long long nz2 = __ballot(lv > 0.0);
+    const int l2 = hit2 ? (__ffsll((long long)hit2) - 1) : (nz2 ? (63 - __clzll((long long)nz2)) : 0);
+    if (lane != l2) return;
+
+    float x[EPV];
+    unpack<DT>(hv, x);
+    double ed[EPV];
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) {
+        float e = fast_exp2(fmaf(x[i], k, -rw));
+        if constexpr (HAS_THR) e = (x[i] >= thr) ? e : 0.f;
+        ed[i] = (double)ldexpf(e, shf);
+    }
+    double acc = incl2 - lv;
+    int ih = -1, ilast = 0;
+    double before = acc, before_last = acc, ev = 0.0, ev_last = 0.0;
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) {
+        if (ed[i] > 0.0) { ilast = i; before_last = acc; ev_last = ed[i]; }
+        if (ih < 0 && acc + ed[i] > tau) { ih = i; before = acc; ev = ed[i]; }
+        acc += ed[i];
+    }
+    if (ih < 0) { ih = ilast; before = before_last; ev = ev_last; }
+
+    int64_t tok64 = ((int64_t)v0 + (int64_t)cj * 64 + lane) * EPV + ih;
+    if (tok64 > a.V - 1) tok64 = a.V - 1;
+    RowOut o;
+    o.token = (int32_t)tok64;
+    o.c_next = rescale_code(tau, before, ev);
+    o.prob = 0.f;
+    o.f_lo = 0.f;
+    if (a.prob_out || a.flo_out) {          // records for tests and callers that ask: fp32 quotients of fp64 sums
+        const float Sf = (float)S;
+        o.prob = (float)ev / Sf;
+        o.f_lo = (float)before / Sf;
+    }
+    write_row(a, r, o);
+}
+
+// ===========================================================================
 // generic kernel: any alignment, any V.  Three plain passes over the row (max,
 // sums, search), each thread owning one contiguous run of elements so that
 // thread order is vocabulary order.  Slow; meant for odd shapes only.
@@ -539,7 +794,9 @@ as_status launch_shape(as_ctx *ctx, const StepArgs &a)
     const int ntiles = (int)((nvec + tile - 1) / tile);
     const size_t lds = ((size_t)NW * ITERS * 64 + (size_t)ntiles * NW * 2) * sizeof(float);
     if (lds > 60 * 1024) return fail(ctx, AS_ERR_UNSUPPORTED, "vocabulary too large for the share table");
-    if (!whole)
+    if (whole && ntiles == 1 && NW == 4 && ITERS == 16 && ctx->step_shape == 0)
+        launch(ctx, kKernelStep, step_tile_kernel<DT, HAS_THR>, dim3((unsigned)a.rows), dim3(256), 0, a);
+    else if (!whole)
         launch(ctx, kKernelStep, step_kernel<DT, NW, ITERS, OCC, HAS_THR, true>, dim3((unsigned)a.rows), dim3(NW * 64),
                lds, a, ntiles);
     else
@@ -558,6 +815,7 @@ as_status launch_fast(as_ctx *ctx, const StepArgs &a)
     case 3: return launch_shape<DT, 4, 8, 6, HAS_THR>(ctx, a);
     case 4: return launch_shape<DT, 2, 16, 4, HAS_THR>(ctx, a);
     case 5: return launch_shape<DT, 1, 32, 2, HAS_THR>(ctx, a);
+    case 6: return launch_shape<DT, 4, 16, 4, HAS_THR>(ctx, a);    // the default shape without the single-tile kernel
     default: return launch_shape<DT, 4, 16, 4, HAS_THR>(ctx, a);
     }
 }

@@ -217,6 +217,40 @@ def test_step_shape_sweep(V, dtype):
                    sigma=float(rng.choice([0.5, 3.0, 8.0])), seed=int(rng.integers(1, 1 << 30)))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_single_tile_kernel_edges(dtype):
+    """Rows of whole vectors that fit one tile take a kernel of their own, with one reference per wave taken
+    from the share's first chunk: rows on which that reference is far off (a first chunk that is all -inf or
+    tiny against what follows, so that the weights overflow fp32 and the block falls back to the plain routine),
+    shares that start past the row's end, a ragged last share, keep thresholds from the two-kernel path; and the
+    general kernel on the same rows (its knob), which the single-tile one replaces by default."""
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    V = 32128 if dtype == "bf16" else 16000
+    R = 10
+    rng = np.random.default_rng(91)
+    x = rng.normal(0.0, 3.0, (R, V)).astype(np.float32)
+    x[0, :600] = -80.0; x[0, 700] = 80.0              # first chunk of wave 0 tiny, a huge logit later in the share
+    x[1, :9000] = -np.inf                             # wave 0's first chunks all -inf, its share not
+    x[2, :] = -np.inf; x[2, V - 1] = 1.0              # only the last token
+    x[3, 8192:8192 + 512] = -np.inf                   # wave 1's first chunk all -inf
+    x[4, :] = -60.0; x[4, 5000] = 70.0; x[4, 20000 % V] = 69.5
+    x[5, 1::2] = -np.inf
+    x[6, :] = 0.25                                    # flat
+    stored = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    codes = synth.uniform_codes(R, seed=92)
+    for temp, top_k, top_p in [(1.0, 0, 1.0), (0.5, 0, 1.0), (0.05, 0, 1.0), (1.0, 300, 1.0), (1.0, 0, 0.9)]:
+        for shape in (0, 6):
+            label = f"single tile {dtype} temp={temp} k={top_k} p={top_p} shape={shape}"
+            print("case", label, flush=True)
+            gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, tuning={"step_shape": shape})
+            ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p)
+            print("   ", compare_step(gpu, ref, V, label, trunc=True, codes=codes), flush=True)
+    # short rows: shares wholly past the row's end, and a ragged last share
+    for Vs in (8, 512, 520, 8192, 8200, 16384 if dtype == "f32" else 32768):
+        for shape in (0, 6):
+            _check(Vs, 9, dtype, temp=0.8, seed=Vs, tuning={"step_shape": shape})
+
+
 def test_step_three_pass_kernel():
     # the plain three-pass kernel, which no shape needs any more, forced by its knob
     _check(1001, 24, "bf16", seed=41, tuning={"step_shape": 9})
