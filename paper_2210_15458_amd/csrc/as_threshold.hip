@@ -1221,6 +1221,359 @@ __global__ __launch_bounds__(kThreads) void threshold_stream_kernel(const void *
 
 }  // namespace
 
+// ------------------------------------------------------------ top-k step, single tile
+//
+// Top-k (k up to kTileTopK, optionally followed by the nucleus) and the sampling step for bf16 rows of whole,
+// aligned 16-byte pieces that fit one tile of 64 KiB: four waves of 16 KiB each, the loads and the early look at
+// the finished flag as in the single-tile sampling kernel.  Nothing per logit but integer work, and after the
+// row has landed nothing that waits for memory:
+//   * a stored bf16 becomes an order-preserving signed 16-bit key, two to a register (three packed
+//     instructions per register); a lane keeps the packed maximum of each of its 16 pieces and of all of them.
+//   * the k-th largest of the block's 256 lane maxima, found by every wave by bisection between the smallest
+//     and the largest of them (four ballot counts per round), is at or below the k-th largest logit, and for
+//     anything but adversarial rows only a few more than k logits reach it.
+//   * a piece whose packed maximum reaches that bound (a wave-uniform test per piece, mostly not taken) goes to
+//     LDS whole, 16 bytes and its position, into a table of the wave's own (no atomics: slots come from the
+//     wave's ballot).
+//   * one wave finishes the step with no further barrier: a lane per hot piece takes it apart and the logits
+//     that reach the bound become the candidates, at most 64, a candidate per lane; two passes over the table
+//     (every lane reads every candidate, broadcast reads) give each candidate the number and the weight of the
+//     keys above its own (top-k with ties, nucleus with whole groups) and then the mass before it in
+//     vocabulary order; the bucket of the code and the rescaling follow (Sec. 4.1 loop body).  fp64 sums.
+// A table that overflows (heavy ties, flat rows) sends the block to the radix select and the plain three-pass
+// step, as in the resident kernel.
+constexpr int kTileTopK = 48;
+constexpr int kTileCand = 64;
+
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_i16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2, a), __builtin_bit_cast(i16x2, b)));
+}
+// two stored bf16 -> two signed 16-bit keys in the same order as the values (negative values have their
+// magnitude bits flipped); its own inverse
+__device__ __forceinline__ uint32_t pk_key_bf16(uint32_t w)
+{
+    const i16x2 v = __builtin_bit_cast(i16x2, w);
+    const uint32_t neg = __builtin_bit_cast(uint32_t, v >> 15);      // 0xffff in each negative half
+    return w ^ (neg & 0x7fff7fffu);
+}
+__device__ __forceinline__ float key_to_float(int32_t key)
+{
+    const uint32_t k16 = (uint32_t)key & 0xffffu;
+    const uint32_t bits = (k16 & 0x8000u) ? (k16 ^ 0x7fffu) : k16;
+    return __builtin_bit_cast(float, bits << 16);
+}
+// lanes below this one among those set in `mask`
+__device__ __forceinline__ uint32_t rank_in(unsigned long long mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+struct TileTopK {
+    int32_t lane_max[kThreads];                          // key of the largest logit of every lane
+    uint32_t hot_vec[kThreads / 64][kTileCand][4];       // pieces that hold a logit at or above the bound, per wave
+    int32_t hot_pos[kThreads / 64][kTileCand];           // vocabulary index of their first logit
+    int32_t hot_n[kThreads / 64];
+    // the candidates: key, vocabulary index, weight (sentinels behind the last: lowest key, largest index, no weight)
+    __attribute__((aligned(16))) int32_t ckey[kTileCand];
+    __attribute__((aligned(16))) int32_t cidx[kTileCand];
+    __attribute__((aligned(16))) double cw[kTileCand];
+};
+
+template <bool HAS_P>
+__global__ __launch_bounds__(kThreads, 4) void topk_tile_kernel(StepArgs a, int32_t top_k, float top_p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr int NW = 4, ITERS = 16, G = 4, NG = ITERS / G, EPV = 8;
+    constexpr int kShare = ITERS * 64;
+    constexpr uint32_t kLowest = 0x80008000u;            // below the key of every stored value, twice: never a candidate
+    // the tables of this kernel and the scratch of the general path it falls back to are never live together
+    __shared__ union Shared {
+        Scratch sc;
+        TileTopK tk;
+        __device__ Shared() {}
+    } sh;
+    Scratch &sc = sh.sc;
+    TileTopK &tk = sh.tk;
+
+    const int64_t r = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    uint32_t fin_word = 0u, fin_at = 0u;
+    if (a.finished_in != nullptr) {
+        const uint8_t *q = a.finished_in + r;
+        fin_at = (uint32_t)(reinterpret_cast<uintptr_t>(q) & 3u);
+        fin_word = *reinterpret_cast<const uint32_t *>(q - fin_at);
+    }
+    const float code = a.codes[r];
+    const int64_t src = a.row_ids ? (int64_t)a.row_ids[r] : r;
+    const uint16_t *row = reinterpret_cast<const uint16_t *>(a.logits) + src * a.ld;
+    const unsigned char *rowb = reinterpret_cast<const unsigned char *>(row);
+    const int32_t V = a.V;
+    const int32_t nvec = V / EPV;
+    const int32_t v0 = wave * kShare;
+    u32x4 raw[ITERS];
+    int32_t mych = (nvec - v0 - lane + 63) >> 6;
+    mych = mych < 0 ? 0 : (mych > ITERS ? ITERS : mych);
+    const bool live = v0 < nvec;
+    const bool ragged = v0 + kShare > nvec;
+    const unsigned char *base = rowb + (size_t)(live ? v0 : 0) * 16u;
+    const uint32_t off0 = (uint32_t)lane * 16u;
+    const uint32_t off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
+    auto request_group = [&](int g) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jj = 0; jj < G; ++jj) {
+            uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+            off = off < off_last ? off : off_last;
+            raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+        }
+    };
+    if (live) request_group(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (((fin_word >> (8u * fin_at)) & 0xffu) != 0u) {
+        if (threadIdx.x == 0) write_finished(a, r);
+        return;
+    }
+    uint32_t vm[ITERS];                    // packed maximum of each piece
+    uint32_t lm = kLowest;
+    if (live) {
+#pragma unroll
+        for (int g = 1; g < NG; ++g) request_group(g);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < ITERS; ++j) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) raw[j][i] = pk_key_bf16(raw[j][i]);
+            if (ragged) {
+                // a lane past the row's end has re-read one of its earlier pieces: no logit there
+#pragma unroll
+                for (int i = 0; i < 4; ++i) raw[j][i] = j < mych ? raw[j][i] : kLowest;
+            }
+            vm[j] = pk_max_i16(pk_max_i16(raw[j][0], raw[j][1]), pk_max_i16(raw[j][2], raw[j][3]));
+            lm = pk_max_i16(lm, vm[j]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITERS; ++j) {
+            raw[j] = u32x4{kLowest, kLowest, kLowest, kLowest};
+            vm[j] = kLowest;
+        }
+    }
+    {
+        const int32_t hi = (int32_t)lm >> 16, lo = (int32_t)(lm << 16) >> 16;
+        tk.lane_max[threadIdx.x] = hi > lo ? hi : lo;
+    }
+    __syncthreads();
+
+    // ---------------- every wave: the k-th largest of the 256 lane maxima (four per lane), by bisection between
+    // the smallest and the largest of them (keys as unsigned: + 32768); a round is four ballot counts
+    int32_t bound;
+    {
+        uint32_t m4[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m4[i] = (uint32_t)(tk.lane_max[i * 64 + lane] + 32768);
+        const uint32_t mx = max(max(m4[0], m4[1]), max(m4[2], m4[3]));
+        const uint32_t mn = min(min(m4[0], m4[1]), min(m4[2], m4[3]));
+        // (16-bit integers are exact as floats)
+        uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_max((float)mx));
+        uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)-wave_max(-(float)mn));
+        // at least k of the maxima are >= lo (k <= 256), fewer than k are > hi
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1u) >> 1;
+            int cnt = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cnt += __builtin_popcountll(__ballot(m4[i] >= mid));
+            if (cnt >= top_k) lo = mid;
+            else hi = mid - 1u;
+        }
+        bound = (int32_t)lo - 32768;       // the largest value that at least k lane maxima reach
+    }
+    // pieces that hold a logit at or above the bound go to the wave's table; `below` is bound - 1 in both halves
+    const bool no_bound = bound <= -32768;  // fewer than k lanes hold anything: no bound this way
+    int32_t wc = 0;                         // pieces in the wave's table so far (wave-uniform)
+    if (!no_bound) {
+        const uint32_t b16 = (uint32_t)(bound - 1) & 0xffffu;
+        const uint32_t below = b16 | (b16 << 16);
+#pragma unroll
+        for (int j = 0; j < ITERS; ++j) {
+            const bool hot = pk_max_i16(vm[j], below) != below;
+            const unsigned long long hm = __ballot(hot);
+            if (hm != 0ull) {
+                const uint32_t slot = (uint32_t)wc + rank_in(hm);
+                if (hot && slot < (uint32_t)kTileCand) {
+                    *reinterpret_cast<u32x4 *>(tk.hot_vec[wave][slot]) = raw[j];
+                    tk.hot_pos[wave][slot] = (v0 + j * 64 + lane) * EPV;
+                }
+                wc += __builtin_popcountll(hm);
+            }
+        }
+    }
+    if (lane == 0) tk.hot_n[wave] = no_bound ? kTileCand + 1 : wc;
+    __syncthreads();
+
+    // ---------------- every wave: a lane per hot piece takes it apart; how many logits reach the bound
+    int32_t nh[NW], nhot = 0;
+    bool fall = false;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        nh[w] = tk.hot_n[w];
+        fall = fall || nh[w] > kTileCand;
+        nhot += nh[w];
+    }
+    fall = fall || nhot > kTileCand;
+    int32_t pkey[EPV];
+    int32_t ppos = 0;
+    int ncand = 0;
+    if (!fall) {
+        int w = 0, sl = lane;
+#pragma unroll
+        for (int q = 0; q < NW - 1; ++q) {
+            if (w == q && sl >= nh[q]) { sl -= nh[q]; w = q + 1; }
+        }
+        const bool have = lane < nhot;
+        u32x4 pv = u32x4{kLowest, kLowest, kLowest, kLowest};
+        if (have) {
+            pv = *reinterpret_cast<const u32x4 *>(tk.hot_vec[w][sl]);
+            ppos = tk.hot_pos[w][sl];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pkey[2 * i] = (int32_t)(pv[i] << 16) >> 16;
+            pkey[2 * i + 1] = (int32_t)pv[i] >> 16;
+        }
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) ncand += __builtin_popcountll(__ballot(have && pkey[e] >= bound));
+        fall = ncand > kTileCand;
+    }
+    if (fall) {
+        // ties or a flat row: the general selection, then the plain step (every thread of the block)
+        __syncthreads();                   // the tables give way to the general path's scratch
+        const uint32_t thr_key = radix_threshold<AS_BF16>(sc.radix, row, V, a.temp, top_k, HAS_P ? top_p : 1.f);
+        __syncthreads();
+        generic_step_row<uint16_t>(a, r, Key<AS_BF16>::from_key(thr_key), sc.gen);
+        return;
+    }
+    if (wave != 0) return;
+
+    // ---------------- one wave: the candidates, one per lane
+    {
+        int32_t at = 0;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            const bool hit = lane < nhot && pkey[e] >= bound;
+            const unsigned long long m = __ballot(hit);
+            if (hit) {
+                const uint32_t slot = (uint32_t)at + rank_in(m);
+                tk.ckey[slot] = pkey[e];
+                tk.cidx[slot] = ppos + e;
+            }
+            at += __builtin_popcountll(m);
+        }
+        if (lane >= ncand) {
+            tk.ckey[lane] = -32768;
+            tk.cidx[lane] = 0x7fffffff;
+        }
+    }
+    const bool valid = lane < ncand;
+    const int32_t key = tk.ckey[lane];
+    const int32_t idx = tk.cidx[lane];
+    const float x = key_to_float(key);
+    const float ks = a.k;
+    const float ref = fmaxf(ceilf(wave_max(valid ? x * ks : -__builtin_inff())), kRefFloor);
+    const float w0 = valid ? fast_exp2(fmaf(x, ks, -ref)) : 0.f;
+    tk.cw[lane] = (double)w0;
+    // pass over the table by key: how many candidates, and how much weight, lie above this one's key.  Every
+    // logit at or above the bound is in the table, so ranks in the table are ranks in the row: a candidate is
+    // among the k highest (ties at the k-th all stay) if fewer than k keys are above its own; the nucleus keeps
+    // it if the weight above its key has not reached top_p of the survivors' total (the group of equal keys
+    // that closes the nucleus stays whole).  Groups of four behind the last candidate are skipped.
+    typedef double f64x2 __attribute__((ext_vector_type(2)));
+    int32_t ngt = 0;
+    double above[2] = {0.0, 0.0};
+    auto by_key = [&](int g0, int g1) __attribute__((always_inline)) {
+#pragma unroll
+        for (int g = g0; g < g1; ++g) {
+            const i32x4 kj = *reinterpret_cast<const i32x4 *>(&tk.ckey[4 * g]);
+            f64x2 wj[2];
+            if constexpr (HAS_P) {
+                wj[0] = *reinterpret_cast<const f64x2 *>(&tk.cw[4 * g]);
+                wj[1] = *reinterpret_cast<const f64x2 *>(&tk.cw[4 * g + 2]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool gt = kj[i] > key;
+                ngt += gt ? 1 : 0;
+                if constexpr (HAS_P) above[i & 1] = fma(gt ? 1.0 : 0.0, wj[i >> 1][i & 1], above[i & 1]);
+            }
+        }
+    };
+    constexpr int kMostGroups = (kTileTopK + 3) / 4;     // what a row without ties at the bound needs
+    by_key(0, kMostGroups);
+    if (ncand > 4 * kMostGroups) by_key(kMostGroups, kTileCand / 4);
+    bool kept = valid && ngt < top_k;
+    if constexpr (HAS_P) {
+        const double total = wave_sum((double)(kept ? w0 : 0.f));
+        kept = kept && !(above[0] + above[1] >= (double)top_p * total);
+    }
+    const float w = kept ? w0 : 0.f;
+    tk.cw[lane] = (double)w;
+    const double S = wave_sum((double)w);
+    // pass by vocabulary index: the mass before every candidate
+    double before[2] = {0.0, 0.0};
+    auto by_index = [&](int g0, int g1) __attribute__((always_inline)) {
+#pragma unroll
+        for (int g = g0; g < g1; ++g) {
+            const i32x4 ij = *reinterpret_cast<const i32x4 *>(&tk.cidx[4 * g]);
+            const f64x2 wa = *reinterpret_cast<const f64x2 *>(&tk.cw[4 * g]);
+            const f64x2 wb = *reinterpret_cast<const f64x2 *>(&tk.cw[4 * g + 2]);
+            before[0] = fma(ij[0] < idx ? 1.0 : 0.0, wa[0], before[0]);
+            before[1] = fma(ij[1] < idx ? 1.0 : 0.0, wa[1], before[1]);
+            before[0] = fma(ij[2] < idx ? 1.0 : 0.0, wb[0], before[0]);
+            before[1] = fma(ij[3] < idx ? 1.0 : 0.0, wb[1], before[1]);
+        }
+    };
+    by_index(0, kMostGroups);
+    if (ncand > 4 * kMostGroups) by_index(kMostGroups, kTileCand / 4);
+    const double bef = before[0] + before[1];
+    const double tau = (double)code * S;
+    const bool has_weight = kept && w > 0.f;
+    unsigned long long sel = __ballot(has_weight && bef <= tau && tau < bef + (double)w);
+    if (sel == 0ull) {
+        // the code at the very top by rounding: the last kept token of the vocabulary
+        int32_t best = has_weight ? idx : -1;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const int32_t o = __shfl_xor(best, d, 64);
+            best = o > best ? o : best;
+        }
+        sel = __ballot(has_weight && idx == best);
+    }
+    if (sel == 0ull) {
+        // no kept candidate with weight: cannot happen for finite logits; leave a valid row behind
+        if (lane == 0) {
+            RowOut o;
+            o.token = 0;
+            o.c_next = rescale_code(0.0, 0.0, 1.0);
+            o.prob = 0.f;
+            o.f_lo = 0.f;
+            write_row(a, r, o);
+        }
+        return;
+    }
+    if (lane == (int)__builtin_ctzll(sel)) {
+        RowOut o;
+        o.token = idx;
+        o.c_next = rescale_code(tau, bef, (double)w);
+        o.prob = (float)((double)w / S);
+        o.f_lo = (float)(bef / S);
+        write_row(a, r, o);
+    }
+}
+
 template <int DT>
 void launch_resident(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, const uint8_t *finished_in,
                      const int32_t *row_ids, float temp, int32_t top_k, float top_p, float *thr_out, bool has_k,
@@ -1245,12 +1598,19 @@ bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p
     const size_t esz = ctx->dtype == AS_BF16 ? 2 : 4;
     const bool has_k = top_k > 0 && top_k < ctx->V, has_p = top_p > 0.f && top_p < 1.f;
     const bool nucleus_only = !has_k && has_p && ctx->dtype == AS_BF16;
-    if (ctx->thr_path != 0 || !(has_k || nucleus_only) || top_k > kThreads / 2 || ctx->V > 32768 ||
+    if ((ctx->thr_path != 0 && ctx->thr_path != 2) || !(has_k || nucleus_only) || top_k > kThreads / 2 || ctx->V > 32768 ||
         reinterpret_cast<uintptr_t>(a.logits) % 16 != 0 || (a.ld * esz) % 16 != 0)
         return false;
     *st = AS_OK;
     if (a.rows == 0) return true;
     const dim3 grid((unsigned)a.rows), block(kThreads);
+    if (has_k && top_k <= kTileTopK && ctx->dtype == AS_BF16 && ctx->V % 8 == 0 && ctx->thr_path != 2) {
+        if (has_p) launch(ctx, kKernelStep, topk_tile_kernel<true>, grid, block, 0, a, top_k, top_p);
+        else launch(ctx, kKernelStep, topk_tile_kernel<false>, grid, block, 0, a, top_k, top_p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) *st = hip_fail(ctx, e, "top-k step launch");
+        return true;
+    }
     if (nucleus_only) {
         launch(ctx, kKernelStep, threshold_resident_kernel<AS_BF16, false, true, true>, grid, block, 0, a.logits, a.ld,
                ctx->V, a.finished_in, a.row_ids, a.temp, top_k, top_p, (float *)nullptr, a);

@@ -251,6 +251,66 @@ def test_step_single_tile_kernel_edges(dtype):
             _check(Vs, 9, dtype, temp=0.8, seed=Vs, tuning={"step_shape": shape})
 
 
+def test_step_topk_single_tile_kernel_edges():
+    """bf16 rows of whole vectors that fit one tile, top-k up to 48 (with or without the nucleus), take a kernel
+    of their own that bounds the k-th largest logit by the k-th largest of its 256 lane maxima and finishes on at
+    most 64 candidates: the smallest and largest k it takes and the first it does not, rows that fill whole
+    tiles, one piece, ragged last shares and shares past the row's end; rows whose candidates overflow its
+    tables (ties at the bound, flat rows, two-valued rows) and hand over to the general selection; rows with
+    fewer live tokens than k; all-negative rows; rows picked through row ids with finished rows among them.
+    The register-resident kernel it replaces by default runs on the same rows (its knob) and must give the same
+    tokens."""
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    V, R = 32128, 14
+    rng = np.random.default_rng(191)
+    x = rng.normal(0.0, 3.0, (R, V)).astype(np.float32)
+    x[0, :] = 1.25                                   # every logit equal
+    x[1, :] = np.round(x[1, :])                      # heavy ties at the bound
+    x[2, :] *= 0.001                                 # flat
+    x[3, 30:] = -np.inf                              # fewer live tokens than k
+    x[4, :] = -np.abs(x[4, :]) - 0.5                 # all negative
+    x[5, :] = -30.0; x[5, 17] = 5.0                  # one-hot
+    x[6, :] = np.where(rng.random(V) < 0.5, 2.0, -2.0)
+    x[7, :64] = 25.0 + np.arange(64) * 0.125         # the whole top in one chunk of one wave
+    x[8, ::512] = 20.0                               # the top spread one logit per chunk, all equal
+    own = ((np.arange(16)[:, None] * 64 + 5) * 8 + np.arange(8)[None, :]).ravel()   # what one lane of the first wave holds
+    x[9, own[:60]] = 30.0 + rng.random(60).astype(np.float32)       # the whole top in that lane: its maximum says little
+    x[10, V - 8:] = 40.0                             # the top in the row's last piece
+    x[11, :] = -np.inf; x[11, 777] = 0.0             # a single live token
+    stored = synth.f32_to_bf16_bits(x)
+    codes = synth.uniform_codes(R, seed=192)
+    for temp, top_k, top_p in [(1.0, 1, 1.0), (1.0, 2, 1.0), (1.0, 40, 1.0), (0.7, 48, 1.0), (1.0, 49, 1.0),
+                               (1.0, 40, 0.9), (1.3, 48, 0.5), (1.0, 7, 0.999), (1.0, 3, 1e-6)]:
+        toks = {}
+        for path in (0, 2):
+            label = f"top-k tile k={top_k} p={top_p} temp={temp} thr_path={path}"
+            print("case", label, flush=True)
+            gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p, tuning={"thr_path": path})
+            ref = oracle_step(stored, codes, V, temp=temp, top_k=top_k, top_p=top_p)
+            print("   ", compare_step(gpu, ref, V, label, trunc=True, codes=codes), flush=True)
+            toks[path] = gpu["token"]
+        assert (toks[0] == toks[2]).mean() >= (R - 1) / R, (toks[0], toks[2])
+    # other widths of one tile: a single piece, a share and a bit, whole tiles, rows that end inside the last share
+    for Vs in (8, 64, 520, 8192, 8200, 16392, 32760, 32768):
+        for top_k, top_p in ((5, 1.0), (40, 0.95), (48, 1.0)):
+            _check(Vs, 9, "bf16", temp=0.9, top_k=min(top_k, Vs - 1), top_p=top_p, seed=Vs + top_k)
+    # gathered rows, finished rows and the end-of-sequence flag
+    LR, R2 = 6, 50
+    st = synth.gaussian_logits(LR, V, seed=193, dtype="bf16")
+    wide = synth.bf16_bits_to_f32(st).copy()
+    wide[:, 1] += 13.0
+    st = synth.f32_to_bf16_bits(wide)
+    rid = rng.integers(0, LR, R2).astype(np.int32)
+    fin = (rng.random(R2) < 0.3).astype(np.uint8)
+    c2 = synth.uniform_codes(R2, seed=194)
+    for top_k, top_p in ((40, 1.0), (12, 0.8)):
+        gpu = run_gpu_step(st, c2, V, top_k=top_k, top_p=top_p, finished=fin, eos_id=1, row_ids=rid)
+        ref = oracle_step(st, c2, V, top_k=top_k, top_p=top_p, finished=fin, eos_id=1, row_ids=rid)
+        print("   ", compare_step(gpu, ref, V, f"top-k tile gathered k={top_k} p={top_p}", trunc=True, codes=c2, eos_id=1),
+              flush=True)
+        assert (gpu["finished"][fin != 0] == 1).all()
+
+
 def test_step_three_pass_kernel():
     # the plain three-pass kernel, which no shape needs any more, forced by its knob
     _check(1001, 24, "bf16", seed=41, tuning={"step_shape": 9})
