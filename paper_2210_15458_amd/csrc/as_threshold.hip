@@ -26,6 +26,7 @@
 
 #include "as_common.hpp"
 #include "as_row.hpp"
+#include "as_tile.hpp"
 
 namespace as {
 namespace {
@@ -1574,6 +1575,311 @@ __global__ __launch_bounds__(kThreads, 4) void topk_tile_kernel(StepArgs a, int3
     }
 }
 
+// ------------------------------------------------------------ nucleus step, single tile
+//
+// The nucleus alone (no top-k) and the sampling step for bf16 rows of whole, aligned 16-byte pieces that fit one
+// tile.  A bf16 logit has one of 65536 values and its weight depends on nothing else, so the mass of a group of
+// equal logits is a count times one weight: the kernel counts, it does not add weights per logit.
+//   * while the row lands (loads and the look at the finished flag as in the single-tile sampling kernel) every
+//     logit goes into a table of counters in LDS, one per stored value in a window of kNucBins values that ends
+//     kNucMargin values (three factors of two) above the largest logit of the row's first chunks; values of the
+//     other sign or below the window go to a counter per lane that nobody reads.  Alongside, the sums of all
+//     weights per chunk, against one integer reference per wave, as in the sampling kernel (for the total).
+//   * after the barrier: 8 counters per thread become masses (count x weight of that value), a scan over the
+//     block finds the first value, from the top, at which the running mass reaches top_p of the total: the keep
+//     threshold; the group of equal logits that closes the nucleus stays whole (its counter is one group).
+//   * the counters give way to a table of weights, one per kept value: the chunk sums of the kept logits are
+//     look-ups and additions, and the search for the code's bucket over them is the sampling kernel's.
+// The row stays in registers throughout.  A logit above the window, a nucleus that does not close inside it (it
+// would have to reach down by a factor of 2^13 or across zero), sums beyond fp32: the block takes the general
+// selection and the plain three-pass step instead.
+constexpr int kNucBins = 2048;
+#ifndef AS_NUC_AHEAD
+#define AS_NUC_AHEAD 4
+#endif
+constexpr int kNucAhead = AS_NUC_AHEAD;  // groups of four loads requested ahead of the group being counted
+constexpr int kNucMargin = 384;
+
+struct TileNucleus {
+    __attribute__((aligned(16))) uint32_t hist[kNucBins + 64];
+    TileSums sums;
+    double wave_tot[kThreads / 64];
+    int32_t anchor[kThreads / 64];
+    int32_t over[kThreads / 64];
+    int32_t pick[kThreads / 64];
+};
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, a) - __builtin_bit_cast(u16x2, b)));
+}
+
+__global__ __launch_bounds__(kThreads, 4) void nucleus_tile_kernel(StepArgs a, float top_p)
+{
+    constexpr int DT = AS_BF16;
+    constexpr int NW = kTileWaves, ITERS = kTileIters, G = kTileGroup, NG = ITERS / G, EPV = 8;
+    constexpr int kShare = ITERS * 64;
+    __shared__ union Shared {
+        Scratch sc;
+        TileNucleus tn;
+        __device__ Shared() {}
+    } sh;
+    Scratch &sc = sh.sc;
+    TileNucleus &tn = sh.tn;
+
+    const int64_t r = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    uint32_t fin_word = 0u, fin_at = 0u;
+    if (a.finished_in != nullptr) {
+        const uint8_t *q = a.finished_in + r;
+        fin_at = (uint32_t)(reinterpret_cast<uintptr_t>(q) & 3u);
+        fin_word = *reinterpret_cast<const uint32_t *>(q - fin_at);
+    }
+    const float code = a.codes[r];
+    const int64_t src = a.row_ids ? (int64_t)a.row_ids[r] : r;
+    const uint16_t *row = reinterpret_cast<const uint16_t *>(a.logits) + src * a.ld;
+    const unsigned char *rowb = reinterpret_cast<const unsigned char *>(row);
+    const int32_t V = a.V;
+    const int32_t nvec = V / EPV;
+    const float k = a.k;
+    const int32_t v0 = wave * kShare;
+    u32x4 raw[ITERS];
+    int32_t mych = (nvec - v0 - lane + 63) >> 6;
+    mych = mych < 0 ? 0 : (mych > ITERS ? ITERS : mych);
+    const bool live = v0 < nvec;
+    const bool ragged = v0 + kShare > nvec;
+    const unsigned char *base = rowb + (size_t)(live ? v0 : 0) * 16u;
+    const uint32_t off0 = (uint32_t)lane * 16u;
+    const uint32_t off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
+    auto request_group = [&](int g) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jj = 0; jj < G; ++jj) {
+            uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+            off = off < off_last ? off : off_last;
+            raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+        }
+    };
+    // the counters start at zero (before anything is loaded: the registers of the row are not free later)
+    for (int i = threadIdx.x; i < (kNucBins + 64) / 4; i += kThreads)
+        reinterpret_cast<u32x4 *>(tn.hist)[i] = u32x4{0u, 0u, 0u, 0u};
+    __builtin_amdgcn_sched_barrier(0);
+    // From here to the end of the counting there is one path for every wave, with no branch between the loads
+    // and the code that takes them in (the compiler's wait counters are exact only then).  A share past the
+    // row's end (mych = 0 in every lane) re-reads the row's first piece and counts it for nothing.
+    request_group(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (((fin_word >> (8u * fin_at)) & 0xffu) != 0u) {
+        if (threadIdx.x == 0) write_finished(a, r);
+        return;
+    }
+#pragma unroll
+    for (int g = 1; g < kNucAhead; ++g) request_group(g);
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 *const my_sums = reinterpret_cast<f32x4 *>(tn.sums.chunk_sum + wave * ITERS);
+
+    // ---------------- where the window goes: the largest logit of the four waves' first chunks (as a key that
+    // orders like the values), and a margin above it
+    {
+        const uint32_t m2 = pk_max_i16(pk_max_i16(pk_key_bf16(raw[0][0]), pk_key_bf16(raw[0][1])),
+                                       pk_max_i16(pk_key_bf16(raw[0][2]), pk_key_bf16(raw[0][3])));
+        const int32_t hi = (int32_t)m2 >> 16, lo = (int32_t)(m2 << 16) >> 16;
+        const int32_t km = mych > 0 ? (hi > lo ? hi : lo) : -32768;
+        const float fm = wave_max((float)(km + 32768));      // (16-bit integers are exact as floats)
+        if (lane == 0) tn.anchor[wave] = (int32_t)fm;
+    }
+    __syncthreads();
+    int32_t kb = tn.anchor[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) kb = tn.anchor[w] > kb ? tn.anchor[w] : kb;
+    kb = __builtin_amdgcn_readfirstlane(kb) - 32768;
+    // A stored value v is counted at e - C, where e = v ^ X falls as the logit rises (X flips the magnitude bits
+    // of positive values; negative ones already run that way) and C is e of the window's top.  Values of the
+    // other sign give an e - C beyond the window either way.
+    const bool positive = kb >= 0;
+    int32_t top_raw = kb + kNucMargin;
+    top_raw = top_raw > 0x7f7f ? 0x7f7f : top_raw;           // the largest finite value
+    int32_t top_mag = (-1 - kb) - kNucMargin;
+    top_mag = top_mag < 0 ? 0 : top_mag;
+    const uint32_t X = positive ? 0x7fffu : 0u;
+    const uint32_t C = positive ? 0x7fffu - (uint32_t)top_raw : (0x8000u | (uint32_t)top_mag);
+    bool fall = positive && top_raw < kNucBins - 1;         // a window that would cross zero
+    float rw;
+    uint32_t emin = 0xffffffffu;
+    {
+        const uint32_t X2 = X | (X << 16), C2 = C | (C << 16);
+        const uint32_t NBL = (uint32_t)(kNucBins + lane) * 0x10001u;
+        rw = tile_reference<DT, false, true>(raw[0], k, 0.f, mych);
+        const float nr = -rw;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            if (g + kNucAhead < NG) {
+                request_group(g + kNucAhead);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            float t[G];
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                const int j = g * G + jj;
+                t[jj] = tile_lane_sum<DT, false>(raw[j], k, nr, 0.f);
+                t[jj] = j < mych ? t[jj] : 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t e = raw[j][i] ^ X2;
+                    emin = pk_min_u16(emin, e);
+                    uint32_t d = pk_min_u16(pk_sub_u16(e, C2), NBL);
+                    d = j < mych ? d : NBL;
+                    __hip_atomic_fetch_add(&tn.hist[d & 0xffffu], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    __hip_atomic_fetch_add(&tn.hist[d >> 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                // (a piece at a time, the running minimum in this order: work of several pieces interleaved, or
+                // a minimum taken as a tree at the end, does not fit the registers)
+                asm volatile("" : "+v"(emin));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wave_sum4_in_lane63(t[0], t[1], t[2], t[3]);
+            if (lane == 63) my_sums[g] = f32x4{t[0], t[1], t[2], t[3]};
+        }
+    }
+    {
+        const uint32_t em = min(emin & 0xffffu, emin >> 16);
+        const bool above = em < C;                           // a logit above the window's top (or of the other sign)
+        const unsigned long long any = __ballot(above);
+        if (lane == 0) {
+            tn.over[wave] = any != 0ull;
+            tn.sums.share_ref[wave] = rw;
+        }
+    }
+    __syncthreads();
+
+    // ---------------- every wave: the total of all weights; masses of the counters; where the nucleus closes
+    float R = tn.sums.share_ref[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        R = fmaxf(R, tn.sums.share_ref[w]);
+        fall = fall || tn.over[w] != 0;
+    }
+    fall = fall || tn.over[0] != 0;
+    double need = 0.0;
+    {
+        const float my_ref = tn.sums.share_ref[lane / ITERS];
+        const double cv = (double)ldexpf(tn.sums.chunk_sum[lane], shift_of(my_ref, R));
+        const double S_all = wave_sum(cv);
+        fall = fall || !(S_all < (double)__builtin_inff());
+        need = (double)top_p * S_all;
+    }
+    constexpr int kPer = kNucBins / kThreads;
+    double m[kPer], local = 0.0;
+    float wv[kPer];
+    uint32_t cnt[kPer];
+    {
+        const u32x4 c0 = reinterpret_cast<const u32x4 *>(tn.hist)[threadIdx.x * 2];
+        const u32x4 c1 = reinterpret_cast<const u32x4 *>(tn.hist)[threadIdx.x * 2 + 1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { cnt[i] = c0[i]; cnt[4 + i] = c1[i]; }
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const uint32_t v = ((C + (uint32_t)(threadIdx.x * kPer + i)) ^ X) & 0xffffu;    // the stored value of this counter
+            const float w = fast_exp2(fmaf(bits_f32(v << 16), k, -R));
+            wv[i] = w;
+            m[i] = cnt[i] ? (double)((float)cnt[i] * w) : 0.0;
+            local += m[i];
+        }
+    }
+    const double incl = wave_scan_add(local);
+    if (lane == 63) tn.wave_tot[wave] = incl;
+    __syncthreads();
+    double cum = incl;
+#pragma unroll
+    for (int w = 0; w < NW - 1; ++w) cum += w < wave ? tn.wave_tot[w] : 0.0;
+    {
+        // the first thread, in the order of the values, whose running mass reaches the goal names the counter
+        const unsigned long long hit = __ballot(cum >= need);
+        int32_t mine = -1;
+        if (hit != 0ull && lane == (int)__builtin_ctzll(hit)) {
+            double acc = cum - local;
+            int32_t last = -1;
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                acc += m[i];
+                if (cnt[i]) last = threadIdx.x * kPer + i;
+                if (mine < 0 && cnt[i] && acc >= need) mine = threadIdx.x * kPer + i;
+            }
+            if (mine < 0) mine = last;                       // (the two orders of summation differ in the last place)
+            tn.pick[wave] = mine;
+        }
+        if (hit == 0ull && lane == 0) tn.pick[wave] = -1;
+    }
+    __syncthreads();
+    int32_t pick = -1;
+#pragma unroll
+    for (int w = NW - 1; w >= 0; --w) pick = tn.pick[w] >= 0 ? tn.pick[w] : pick;
+    fall = fall || pick < 0;
+    if (fall) {
+        // the general selection, then the plain step (every thread of the block)
+        __syncthreads();
+        const uint32_t thr_key = radix_threshold<AS_BF16>(sc.radix, row, V, a.temp, 0, top_p);
+        __syncthreads();
+        generic_step_row<uint16_t>(a, r, Key<AS_BF16>::from_key(thr_key), sc.gen);
+        return;
+    }
+    const float thr = bits_f32((((C + (uint32_t)pick) ^ X) & 0xffffu) << 16);
+
+    // ---------------- the chunk sums of the kept logits, and the bucket of the code.  The counters give way to
+    // the weights of their values against the block's reference R (nothing for the values below the threshold
+    // and for the counters outside the window): a kept logit's weight is then a look-up, not an exponential.
+    {
+        float *const wtab = reinterpret_cast<float *>(tn.hist);
+        f32x4 w0, w1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            w0[i] = threadIdx.x * kPer + i <= pick ? wv[i] : 0.f;
+            w1[i] = threadIdx.x * kPer + 4 + i <= pick ? wv[4 + i] : 0.f;
+        }
+        reinterpret_cast<f32x4 *>(wtab)[threadIdx.x * 2] = w0;
+        reinterpret_cast<f32x4 *>(wtab)[threadIdx.x * 2 + 1] = w1;
+        if (threadIdx.x < 16) reinterpret_cast<f32x4 *>(wtab + kNucBins)[threadIdx.x] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (lane == 0) tn.sums.share_ref[wave] = R;          // the sums that follow are relative to R in every wave
+        __syncthreads();
+        const uint32_t X2 = X | (X << 16), C2 = C | (C << 16);
+        // everything below the threshold reads one of the 64 zeros that follow it in the table, each lane its
+        // own: consecutive words, no bank conflicts (most of the row is below the threshold)
+        const uint32_t NBL = (uint32_t)(pick + 1 + lane) * 0x10001u;
+        // (the row's registers made opaque: otherwise every counter index of the first pass is kept, in memory,
+        // for this one)
+#pragma unroll
+        for (int j = 0; j < ITERS; ++j)
+            asm volatile("" : "+v"(raw[j][0]), "+v"(raw[j][1]), "+v"(raw[j][2]), "+v"(raw[j][3]));
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            float t[G];
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                const int j = g * G + jj;
+                float w[EPV];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint32_t d = pk_min_u16(pk_sub_u16(raw[j][i] ^ X2, C2), NBL);
+                    d = j < mych ? d : NBL;
+                    w[2 * i] = wtab[d & 0xffffu];
+                    w[2 * i + 1] = wtab[d >> 16];
+                }
+                t[jj] = vec_sum<EPV>(w);
+            }
+            wave_sum4_in_lane63(t[0], t[1], t[2], t[3]);
+            if (lane == 63) my_sums[g] = f32x4{t[0], t[1], t[2], t[3]};
+        }
+    }
+    __syncthreads();
+    tile_select<DT, true>(a, r, code, thr, raw, R, mych, ragged, v0, lane, wave, tn.sums, sc.gen);
+}
+
 template <int DT>
 void launch_resident(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, const uint8_t *finished_in,
                      const int32_t *row_ids, float temp, int32_t top_k, float top_p, float *thr_out, bool has_k,
@@ -1609,6 +1915,12 @@ bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p
         else launch(ctx, kKernelStep, topk_tile_kernel<false>, grid, block, 0, a, top_k, top_p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) *st = hip_fail(ctx, e, "top-k step launch");
+        return true;
+    }
+    if (nucleus_only && ctx->V % 8 == 0 && ctx->thr_path != 2) {
+        launch(ctx, kKernelStep, nucleus_tile_kernel, grid, block, 0, a, top_p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) *st = hip_fail(ctx, e, "nucleus step launch");
         return true;
     }
     if (nucleus_only) {

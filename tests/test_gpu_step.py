@@ -311,6 +311,59 @@ def test_step_topk_single_tile_kernel_edges():
         assert (gpu["finished"][fin != 0] == 1).all()
 
 
+def test_step_nucleus_single_tile_kernel_edges():
+    """bf16 rows of whole vectors that fit one tile, the nucleus alone, take a kernel that counts logits by stored
+    value in a window of 2048 values placed from the row's first chunks: rows whose largest logit lies far above
+    what the first chunks show (above the window: the block hands over to the general selection), rows of
+    negative logits only (the window runs the other way), negative first chunks with positive logits later,
+    rows whose nucleus reaches across zero or below the window (flat rows, two-valued rows), tiny logits (a window
+    that would cross zero), one live token, heavy ties; widths that leave shares empty or ragged; gathered and
+    finished rows.  The register-resident kernel it replaces by default runs on the same rows (its knob)."""
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    V, R = 32128, 16
+    rng = np.random.default_rng(291)
+    x = rng.normal(0.0, 3.0, (R, V)).astype(np.float32)
+    x[0, 20000] = 200.0                              # far above the window's top
+    x[1, :] = -np.abs(x[1, :]) - 0.25                # negative logits only
+    x[2, :512] = -np.abs(x[2, :512]) - 1.0           # the first chunk of the first wave negative, the rest mixed
+    for w in range(4):                                # every wave's first chunk negative, positive logits later
+        x[3, w * 8192: w * 8192 + 512] = -np.abs(x[3, w * 8192: w * 8192 + 512]) - 1.0
+    x[4, :] *= 0.001                                 # flat: the nucleus is most of the row, on both sides of zero
+    x[5, :] = np.where(rng.random(V) < 0.5, 2.0, -2.0)
+    x[6, :] *= 1e-30                                 # tiny logits
+    x[7, :] = -np.inf; x[7, 4321] = 0.5              # one live token
+    x[8, :] = np.round(x[8, :])                      # heavy ties
+    x[9, :] = np.abs(x[9, :]) + 0.5                  # positive logits only
+    x[10, :] = 1.25                                  # every logit equal
+    x[11, :] = -7.0; x[11, ::97] = -6.5              # negative, two values
+    x[12, :] += 60.0                                 # a large common offset: a few values per factor of two
+    x[13, :] = x[13, :] * 0.05 - 3.0                 # negative and narrow
+    stored = synth.f32_to_bf16_bits(x)
+    codes = synth.uniform_codes(R, seed=292)
+    for temp, top_p in [(1.0, 0.9), (0.7, 0.5), (1.5, 0.99), (1.0, 0.05), (1.0, 1e-6), (0.3, 0.999)]:
+        for path in (0, 2):
+            label = f"nucleus tile p={top_p} temp={temp} thr_path={path}"
+            print("case", label, flush=True)
+            gpu = run_gpu_step(stored, codes, V, temp=temp, top_p=top_p, tuning={"thr_path": path})
+            ref = oracle_step(stored, codes, V, temp=temp, top_p=top_p)
+            print("   ", compare_step(gpu, ref, V, label, trunc=True, codes=codes), flush=True)
+    for Vs in (8, 64, 520, 8192, 8200, 16392, 32760, 32768):
+        for top_p in (0.9, 0.3):
+            _check(Vs, 9, "bf16", temp=0.9, top_p=top_p, seed=Vs + 1)
+    LR, R2 = 6, 50
+    st = synth.gaussian_logits(LR, V, seed=293, dtype="bf16")
+    wide = synth.bf16_bits_to_f32(st).copy()
+    wide[:, 1] += 13.0
+    st = synth.f32_to_bf16_bits(wide)
+    rid = rng.integers(0, LR, R2).astype(np.int32)
+    fin = (rng.random(R2) < 0.3).astype(np.uint8)
+    c2 = synth.uniform_codes(R2, seed=294)
+    gpu = run_gpu_step(st, c2, V, top_p=0.9, finished=fin, eos_id=1, row_ids=rid)
+    ref = oracle_step(st, c2, V, top_p=0.9, finished=fin, eos_id=1, row_ids=rid)
+    print("   ", compare_step(gpu, ref, V, "nucleus tile gathered", trunc=True, codes=c2, eos_id=1), flush=True)
+    assert (gpu["finished"][fin != 0] == 1).all()
+
+
 def test_step_three_pass_kernel():
     # the plain three-pass kernel, which no shape needs any more, forced by its knob
     _check(1001, 24, "bf16", seed=41, tuning={"step_shape": 9})
