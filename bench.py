@@ -57,11 +57,19 @@ def up(a):
 def sampling_kernel_name(V, ldt, top_k, top_p):
     """Which kernel finishes the sampling step for this shape (the choice the library makes)."""
     has_k, has_p = 0 < top_k < V, 0.0 < top_p < 1.0
-    if V <= 32768 and ((has_k and top_k <= 128) or (has_p and not has_k and ldt == "bf16")):
-        return ("threshold_resident_kernel with the sampling step fused (%s), as launched inside as_decode"
-                % ("top-k, candidates ranked in LDS" if has_k else "nucleus alone, row resident in registers"))
+    tile = V <= (32768 if ldt == "bf16" else 16384) and V % (8 if ldt == "bf16" else 4) == 0
+    if tile and ldt == "bf16" and has_k and top_k <= 48:
+        return ("topk_tile_kernel (top-k%s and the sampling step in one launch, row resident in registers), "
+                "as launched inside as_decode" % (" + nucleus" if has_p else ""))
+    if tile and ldt == "bf16" and has_p and not has_k:
+        return ("nucleus_tile_kernel (nucleus and the sampling step in one launch, logits counted by stored value), "
+                "as launched inside as_decode")
+    if V <= 32768 and has_k and top_k <= 128:
+        return "threshold_resident_kernel with the sampling step fused (top-k, candidates ranked in LDS), as launched inside as_decode"
     if has_k or has_p:
-        return "threshold kernel, then step_kernel (fused sampling step), as launched inside as_decode"
+        return "threshold kernel, then the sampling-step kernel, as launched inside as_decode"
+    if tile:
+        return "step_tile_kernel (fused sampling step, one-tile rows), as launched inside as_decode"
     return "step_kernel (fused sampling step), as launched inside as_decode"
 
 
@@ -137,7 +145,7 @@ def source_stamp():
     """Hash of the sources the sampling kernel is built from (ties a stored counter reading to the kernel timed)."""
     here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2210_15458_amd", "csrc")
     h = hashlib.sha256()
-    for name in ("as_step.hip", "as_row.hpp", "as_common.hpp"):
+    for name in ("as_step.hip", "as_tile.hpp", "as_row.hpp", "as_common.hpp"):
         with open(os.path.join(here, name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
@@ -216,6 +224,14 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
+    # a longer region of the same work (the K-step figure moves by a few per cent from box to box and run to run)
+    long_steps = max(100, args.steps)
+    t4 = time.perf_counter()
+    for _ in range(long_steps):
+        decode()
+    torch.cuda.synchronize()
+    t5 = time.perf_counter()
+
     # the same region once more with a start/stop event attached to every kernel
     # dispatch (this costs some launch throughput, so it is kept out of `value`)
     ctx.profile(True)
@@ -256,7 +272,9 @@ def main():
                                f"weights, {ldt} logits, B={Bn} N={N} (R={R}) T={T} temp={temp} top_k={top_k} "
                                f"top_p={top_p} eos={eos}; one step = one whole decode ({R * T} code-steps)",
                    "storage": ldt, "rows": R, "decode_steps": T,
-                   "value_with_dispatch_events": code_steps / (t3 - t2)},
+                   "value_with_dispatch_events": code_steps / (t3 - t2),
+                   "value_over_a_longer_region": {"steps": long_steps, "value": R * T * long_steps / (t5 - t4),
+                                                  "ms_per_step": (t5 - t4) / long_steps * 1e3}},
         "roofline": {
             "kernel": sampling_kernel_name(V, ldt, top_k, top_p),
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
