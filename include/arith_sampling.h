@@ -95,7 +95,7 @@ const char *as_last_error(const as_ctx *ctx);
  *   AS_TUNE_THR_PATH    keep-threshold kernel: 1 = the radix select instead of
  *                       the register-resident / streamed kernels; 2 = the
  *                       register-resident kernel also where the single-tile
- *                       top-k kernel applies
+ *                       top-k and nucleus kernels apply
  *   AS_TUNE_GEMM_GM     persistent logits kernel with more row tiles than
  *                       workers: workers of one XCD along the rows (a divisor
  *                       of the workers per XCD; otherwise ignored)
