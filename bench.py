@@ -134,6 +134,25 @@ def compact_leg(cfg_id, top_k, top_p, steps, warmup):
     out["logits_gemm"]["frac"] = out["logits_gemm"]["achieved"] / MFMA_BF16_PEAK_TFLOPS
     if len(thr_samples):
         out["sampling"]["threshold_kernel_us"] = float(np.mean(thr_samples)) * 1e3
+    if top_k <= 0 and not (0.0 < top_p < 1.0) and R <= 4096:
+        # the same decode without the logits round trip (no logit modifiers; logits stay fp32 on chip)
+        for _ in range(warmup):
+            B.as_decode_fused(ctx, model, prompts, N, T, u, temp, eos, tokens)
+        torch.cuda.synchronize()
+        f0 = time.perf_counter()
+        for _ in range(steps):
+            B.as_decode_fused(ctx, model, prompts, N, T, u, temp, eos, tokens)
+        torch.cuda.synchronize()
+        f1 = time.perf_counter()
+        ctx.profile(True)
+        B.as_decode_fused(ctx, model, prompts, N, T, u, temp, eos, tokens)
+        torch.cuda.synchronize()
+        fs, fg = ctx.profile_samples(0), ctx.profile_samples(1)
+        ctx.profile_read(0); ctx.profile_read(1)
+        ctx.profile(False)
+        out["fused_decode"] = {"value": R * T * steps / (f1 - f0), "unit": "code-steps/s",
+                               "ms_per_decode": (f1 - f0) / steps * 1e3,
+                               "logits_kernel_us": float(np.mean(fg)) * 1e3, "sampling_kernel_us": float(np.mean(fs)) * 1e3}
     ctx.close()
     model.close()
     del Ed, tokens

@@ -292,7 +292,7 @@ as_status as_decode(as_ctx *ctx, const as_model *model, const int32_t *prompts,
  * as_step_fused: one step of Algorithm 1 (Sec. 4.1) from those group masses: finds the
  * group of each row's code, recomputes that group's 32 logits from the model (row
  * prev[r]), finishes the bucket search and rescales the code.  Arguments as in
- * as_step_ex; ldp <= 1024 (V <= 32768).
+ * as_step_ex; ldp <= 65536 (the library's largest vocabulary, 2^21).
  * Both need bf16 weights and a rank d that is a multiple of 64 and at least 128.
  */
 as_status as_bigram_group_mass(as_ctx *ctx, const as_model *model, const int32_t *prev,
@@ -311,7 +311,7 @@ as_status as_step_fused(as_ctx *ctx, const as_model *model, const float *mass, i
  * (they are never rounded to a storage type), so results agree with as_decode on an fp32
  * context only up to the accumulation order.
  * No logit modifiers (top_k / top_p); needs bf16 weights, a rank d that is a multiple of
- * 64 and at least 128, V <= 32768; AS_ERR_UNSUPPORTED otherwise.  Arguments as in as_decode.
+ * 64 and at least 128; AS_ERR_UNSUPPORTED otherwise.  Arguments as in as_decode.
  */
 as_status as_decode_fused(as_ctx *ctx, const as_model *model, const int32_t *prompts,
                           int32_t B, int32_t N, int32_t T, const float *u, float temp,

@@ -520,9 +520,9 @@ as_status as_step_fused(as_ctx *ctx, const as_model *model, const float *mass, i
     if (finished_in && eos_id < 0) return fail(ctx, AS_ERR_INVALID_ARG, "finished_in given without an eos_id to emit");
     if (eos_id >= ctx->V) return fail(ctx, AS_ERR_INVALID_ARG, "eos_id outside the vocabulary");
     const int64_t ngroups = ((int64_t)ctx->V + 31) / 32;
-    if (ldp < ngroups || ldp % 16 != 0 || ldp > 64 * 16 || reinterpret_cast<uintptr_t>(mass) % 16 != 0)
+    if (ldp < ngroups || ldp % 16 != 0 || ldp > 65536 || reinterpret_cast<uintptr_t>(mass) % 16 != 0)
         return fail(ctx, AS_ERR_INVALID_ARG,
-                    "ldp must be a multiple of 16, at most 1024, covering ceil(V/32) groups; mass 16-byte aligned");
+                    "ldp must be a multiple of 16, at most 65536, covering ceil(V/32) groups; mass 16-byte aligned");
     if (!fused_path_applies(ctx, model))
         return fail(ctx, AS_ERR_UNSUPPORTED, "the fused step needs bf16 weights and a rank that is a multiple of 64");
     FusedArgs a{};
@@ -556,7 +556,6 @@ as_status as_decode_fused(as_ctx *ctx, const as_model *model, const int32_t *pro
 
     const int32_t ngroups = (ctx->V + 31) / 32;
     const int64_t ldp = ((int64_t)ngroups + 15) / 16 * 16;
-    if (ldp > 64 * 16) return fail(ctx, AS_ERR_UNSUPPORTED, "the fused decode takes vocabularies up to 32768");
     as_status st = grow(ctx, ctx->logits, (size_t)R * ldp * sizeof(float2));
     if (st != AS_OK) return st;
     st = grow(ctx, ctx->state, (size_t)R * 9);

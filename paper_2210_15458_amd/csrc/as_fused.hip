@@ -16,30 +16,40 @@ constexpr int kGroupsPerLane = 16;
 __device__ __forceinline__ int first_lane(unsigned long long mask) { return __builtin_ctzll(mask); }
 __device__ __forceinline__ int last_lane(unsigned long long mask) { return 63 - __builtin_clzll(mask); }
 
-// One 256-thread block per row.  Wave 0 walks the row's table (read as whole lines, regrouped through LDS so
-// that a lane holds 16 consecutive groups); then all four waves recompute the hit group's 32 logits, a wave
-// reading one whole row of U^T per instruction (8 rows per wave) against the embedding piece it fetched at
-// the start; wave 0 finishes.
+// One 256-thread block per row.  A tile is 1024 groups (a lane of one wave holds 16 consecutive ones, read as
+// whole lines and regrouped through LDS).  Rows of one tile (vocabularies up to 32768): wave 0 walks the row's
+// table.  Longer rows (MULTI): the four waves take the tiles in turn and leave (sum, reference) per tile; wave 0
+// scans those (up to 64: vocabularies up to 2^21), finds the tile of the row's code and walks that one tile
+// again.  Then all four waves recompute the hit group's 32 logits, a wave reading one whole row of U^T per
+// instruction (8 rows per wave) against the embedding piece it fetched at the start; wave 0 finishes.
 constexpr int kMaxPiecesPerLane = 8;          // rank up to 64 * 8 * 8 = 4096
+constexpr int kTileGroups = 64 * kGroupsPerLane;
+constexpr int kMaxTiles = 64;
 
+template <bool MULTI>
 __global__ __launch_bounds__(256) void fused_sample_kernel(FusedArgs a)
 {
-    __shared__ __attribute__((aligned(16))) float2 table[64 * kGroupsPerLane];     // 8 KB
+    __shared__ __attribute__((aligned(16))) float2 table[(MULTI ? 4 : 1) * kTileGroups];     // 8 KB per wave that walks
+    __shared__ double tile_sum[MULTI ? kMaxTiles : 1];
+    __shared__ float tile_ref[MULTI ? kMaxTiles : 1];
     __shared__ float dots[32];
     __shared__ int32_t hit_group;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t r = blockIdx.x;
-    // the row of the table first (it depends on nothing but the row number), whole lines at a time
-    float4 tw[kGroupsPerLane / 2];
     const int nvec = (int)(a.ldp / 2);                            // float4 = two groups
-    if (wave == 0) {
-        const float4 *prow4 = reinterpret_cast<const float4 *>(a.part + r * a.ldp);
+    const int ntiles = MULTI ? (int)((a.ldp + kTileGroups - 1) / kTileGroups) : 1;
+    const float4 *prow4 = reinterpret_cast<const float4 *>(a.part + r * a.ldp);
+    float4 tw[kGroupsPerLane / 2];
+    // a tile of the row's table, whole lines at a time
+    auto load_tile = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < kGroupsPerLane / 2; ++t) {
-            const int i = t * 64 + lane;
+            const int i = tile * (kTileGroups / 2) + t * 64 + lane;
             tw[t] = i < nvec ? prow4[i] : float4{0.f, 0.f, 0.f, 0.f};
         }
-    }
+    };
+    // the first tile first (it depends on nothing but the row number)
+    if (MULTI ? wave < ntiles : wave == 0) load_tile(MULTI ? wave : 0);
     const float c = a.codes[r];
     const int32_t prev = clamp_token(a.prev[r], a.V);
     if (a.finished_in != nullptr && a.finished_in[r] != 0) {
@@ -61,10 +71,16 @@ __global__ __launch_bounds__(256) void fused_sample_kernel(FusedArgs a)
 
     float rw = 0.f;
     double tau2 = 0.0;
-    if (wave == 0) {
-        // regroup through LDS so that a lane holds 16 consecutive groups
+    float2 *const tb = table + (MULTI ? wave * kTileGroups : 0);
+    double gm[kGroupsPerLane];
+    double sl = 0.0;
+    // the tile in tw: regrouped through LDS so that a lane holds 16 consecutive groups; gm = their masses
+    // relative to the tile's reference rw (the largest of its groups' references), sl = the lane's sum
+    auto tile_masses = [&](int tile) __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");       // (earlier reads of this wave's buffer are done)
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int t = 0; t < kGroupsPerLane / 2; ++t) reinterpret_cast<float4 *>(table)[t * 64 + lane] = tw[t];
+        for (int t = 0; t < kGroupsPerLane / 2; ++t) reinterpret_cast<float4 *>(tb)[t * 64 + lane] = tw[t];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -72,27 +88,27 @@ __global__ __launch_bounds__(256) void fused_sample_kernel(FusedArgs a)
         const int g0 = lane * kGroupsPerLane;
 #pragma unroll
         for (int t = 0; t < kGroupsPerLane; t += 2) {
-            const float4 w = reinterpret_cast<const float4 *>(table)[(g0 + t) / 2];
+            const float4 w = reinterpret_cast<const float4 *>(tb)[(g0 + t) / 2];
             pr[t] = float2{w.x, w.y};
             pr[t + 1] = float2{w.z, w.w};
         }
         float rl = -200000.f;
 #pragma unroll
         for (int t = 0; t < kGroupsPerLane; ++t) {
-            if (g0 + t >= a.ngroups) pr[t] = float2{0.f, -200000.f};      // padding of the table
+            if (tile * kTileGroups + g0 + t >= a.ngroups) pr[t] = float2{0.f, -200000.f};      // padding of the table
             rl = fmaxf(rl, pr[t].y);
         }
         rw = wave_max(rl);
-        double gm[kGroupsPerLane];
-        double sl = 0.0;
+        sl = 0.0;
 #pragma unroll
         for (int t = 0; t < kGroupsPerLane; ++t) {
             gm[t] = (double)__builtin_amdgcn_ldexpf(pr[t].x, (int)fmaxf(pr[t].y - rw, -300.f));   // exact
             sl += gm[t];
         }
-        const double incl = wave_scan_add(sl);
-        const double S = read_lane(incl, 63);
-        const double tau = (double)c * S;
+    };
+    // the group of the tile in which tau (in the units of the tile's masses) falls; leaves tau2, the rest of
+    // tau inside that group, and returns the group's number within the tile
+    auto group_in_tile = [&](double tau, double incl) __attribute__((always_inline)) {
         const unsigned long long hit = __ballot(incl > tau);
         const unsigned long long live = __ballot(sl > 0.0);
         const int lstar = hit ? first_lane(hit) : (live ? last_lane(live) : 0);
@@ -116,7 +132,49 @@ __global__ __launch_bounds__(256) void fused_sample_kernel(FusedArgs a)
                 if (t < glast) before += read_lane(gm[t], lstar);
         }
         tau2 = tau1 - before;
-        if (lane == 0) hit_group = lstar * kGroupsPerLane + gstar;
+        return lstar * kGroupsPerLane + gstar;
+    };
+    if constexpr (!MULTI) {
+        if (wave == 0) {
+            tile_masses(0);
+            const double incl = wave_scan_add(sl);
+            const double S = read_lane(incl, 63);
+            const int g = group_in_tile((double)c * S, incl);
+            if (lane == 0) hit_group = g;
+        }
+    } else {
+        // every wave: its tiles' totals
+        for (int tile = wave; tile < ntiles; tile += 4) {
+            if (tile != wave) load_tile(tile);
+            tile_masses(tile);
+            const double St = wave_sum(sl);
+            if (lane == 0) {
+                tile_sum[tile] = St;
+                tile_ref[tile] = rw;
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // a lane per tile: totals brought to the row's reference (exact: powers of two), scanned
+            const float rt = lane < ntiles ? tile_ref[lane] : -200000.f;
+            const float Rg = wave_max(rt);
+            const float down = __builtin_amdgcn_ldexpf(1.f, (int)fmaxf(rt - Rg, -126.f));     // 2^(rt - Rg), 0 below 2^-126
+            const double st = lane < ntiles && rt - Rg >= -126.f ? tile_sum[lane] * (double)down : 0.0;
+            const double tincl = wave_scan_add(st);
+            const double S = read_lane(tincl, 63);
+            const double tau = (double)c * S;
+            const unsigned long long thit = __ballot(tincl > tau);
+            const unsigned long long tlive = __ballot(st > 0.0);
+            const int tstar = thit ? first_lane(thit) : (tlive ? last_lane(tlive) : 0);
+            // the rest of tau inside that tile, in the tile's own units
+            const double rest = tau - (read_lane(tincl, tstar) - read_lane(st, tstar));
+            const float up = __builtin_amdgcn_ldexpf(1.f, (int)fminf(Rg - read_lane(rt, tstar), 126.f));
+            load_tile(tstar);
+            tile_masses(tstar);
+            const double incl = wave_scan_add(sl);
+            const int g = group_in_tile(rest * (double)up, incl);
+            if (lane == 0) hit_group = tstar * kTileGroups + g;
+        }
     }
     __syncthreads();
     const int32_t grp = hit_group;
@@ -183,7 +241,9 @@ as_status launch_fused_sample(as_ctx *ctx, const FusedArgs &a)
 {
     if (a.rows == 0) return AS_OK;
     if (a.d > 64 * 8 * kMaxPiecesPerLane) return fail(ctx, AS_ERR_UNSUPPORTED, "the fused step takes ranks up to 4096");
-    launch(ctx, kKernelStep, fused_sample_kernel, dim3((unsigned)a.rows), dim3(256), 0, a);
+    if (a.ldp > (int64_t)kTileGroups * kMaxTiles) return fail(ctx, AS_ERR_UNSUPPORTED, "the fused step takes vocabularies up to 2^21");
+    if (a.ldp <= kTileGroups) launch(ctx, kKernelStep, fused_sample_kernel<false>, dim3((unsigned)a.rows), dim3(256), 0, a);
+    else launch(ctx, kKernelStep, fused_sample_kernel<true>, dim3((unsigned)a.rows), dim3(256), 0, a);
     AS_HIP_TRY(ctx, hipGetLastError());
     return AS_OK;
 }

@@ -36,7 +36,11 @@ def _oracle_step_rows(E, U, prev, codes, temp, fin, eos):
 
 
 @pytest.mark.parametrize("V,d,Bn,N,T,temp,eos", [(32128, 512, 3, 16, 4, 0.7, 1), (32128, 512, 2, 24, 3, 1.0, -1),
-                                                  (5000, 128, 2, 150, 3, 1.0, 1), (1003, 256, 1, 300, 2, 1.3, 1)])
+                                                  (5000, 128, 2, 150, 3, 1.0, 1), (1003, 256, 1, 300, 2, 1.3, 1),
+                                                  # rows of more than one tile of 1024 groups: one group into
+                                                  # the second tile, two tiles, eight tiles
+                                                  (32800, 128, 2, 40, 2, 0.9, -1), (50257, 256, 2, 32, 3, 1.0, 1),
+                                                  (256000, 256, 1, 24, 2, 1.0, 1)])
 def test_fused_decode_lockstep_against_oracle(V, d, Bn, N, T, temp, eos):
     """Follow the GPU's trajectory: at every step the oracle gets the GPU's conditioning tokens and codes and
     must emit the same token unless the code sits within BAND of a bucket boundary."""
