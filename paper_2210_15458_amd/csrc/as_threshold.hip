@@ -40,7 +40,12 @@ template <> struct Key<AS_BF16> {
     static constexpr int kBits = 16;
     static constexpr int kPasses = 2;
     static __device__ __forceinline__ int width(int p) { return p == 0 ? 12 : 4; }
-    static __device__ __forceinline__ uint32_t key(uint16_t h) { return (uint32_t)(h ^ ((h & 0x8000u) ? 0xffffu : 0x8000u)); }
+    // (-0 and +0 are one value: one key)
+    static __device__ __forceinline__ uint32_t key(uint16_t h)
+    {
+        h = (h & 0x7fffu) ? h : (uint16_t)0;
+        return (uint32_t)(h ^ ((h & 0x8000u) ? 0xffffu : 0x8000u));
+    }
     static __device__ __forceinline__ float value(uint16_t h) { return __builtin_bit_cast(float, (uint32_t)h << 16); }
     static __device__ __forceinline__ float from_key(uint32_t k)
     {
@@ -55,7 +60,8 @@ template <> struct Key<AS_F32> {
     static __device__ __forceinline__ int width(int p) { return p == 2 ? 8 : 12; }
     static __device__ __forceinline__ uint32_t key(float f)
     {
-        const uint32_t b = __builtin_bit_cast(uint32_t, f);
+        uint32_t b = __builtin_bit_cast(uint32_t, f);
+        b = (b << 1) ? b : 0u;                   // (-0 and +0 are one value: one key)
         return b ^ ((b & 0x80000000u) ? 0xffffffffu : 0x80000000u);
     }
     static __device__ __forceinline__ float value(float f) { return f; }
@@ -1392,6 +1398,9 @@ __global__ __launch_bounds__(kThreads, 4) void topk_tile_kernel(StepArgs a, int3
             else hi = mid - 1u;
         }
         bound = (int32_t)lo - 32768;       // the largest value that at least k lane maxima reach
+        // -0 (key -1) and +0 (key 0) are one value: a bound at +0 takes the -0s in as well, and as candidates
+        // both carry the key 0
+        bound = bound == 0 ? -1 : bound;
     }
     // pieces that hold a logit at or above the bound go to the wave's table; `below` is bound - 1 in both halves
     const bool no_bound = bound <= -32768;  // fewer than k lanes hold anything: no bound this way
@@ -1469,7 +1478,7 @@ __global__ __launch_bounds__(kThreads, 4) void topk_tile_kernel(StepArgs a, int3
             const unsigned long long m = __ballot(hit);
             if (hit) {
                 const uint32_t slot = (uint32_t)at + rank_in(m);
-                tk.ckey[slot] = pkey[e];
+                tk.ckey[slot] = pkey[e] == -1 ? 0 : pkey[e];
                 tk.cidx[slot] = ppos + e;
             }
             at += __builtin_popcountll(m);

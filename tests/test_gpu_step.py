@@ -364,6 +364,30 @@ def test_step_nucleus_single_tile_kernel_edges():
     assert (gpu["finished"][fin != 0] == 1).all()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_signed_zero_ties(dtype):
+    """-0 and +0 are one value: tied at the k-th place or in the group that closes the nucleus they stay or go
+    together (the kernels select by integer keys of the stored bits, in which the two differ)."""
+    from gpu_util import compare_step, oracle_step, run_gpu_step
+    rng = np.random.default_rng(391)
+    for V in (8, 1000, 32128):
+        R = 24
+        x = np.round(rng.normal(0.0, 0.3, (R, V)) * 2).astype(np.float32) / 2         # -0.5, -0, +0, 0.5 and a few more
+        x[R // 2:, :] = np.minimum(x[R // 2:, :], 0.0)                                  # rows whose largest value is zero
+        assert np.signbit(x[x == 0]).any() and not np.signbit(x[x == 0]).all()
+        stored = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+        codes = synth.uniform_codes(R, seed=392 + V)
+        for temp, top_k, top_p in [(1.0, 1, 1.0), (0.7, 1, 0.5), (1.0, 5, 1.0), (1.0, 40, 0.9), (1.0, 100, 1.0),
+                                   (1.0, 0, 0.5), (1.0, 0, 0.05), (1.0, 300, 0.3)]:
+            kk = min(top_k, V - 1)
+            for tuning in (None, {"thr_path": 1}, {"thr_path": 2}):
+                label = f"signed zeros {dtype} V={V} temp={temp} k={kk} p={top_p} tuning={tuning}"
+                print("case", label, flush=True)
+                gpu = run_gpu_step(stored, codes, V, temp=temp, top_k=kk, top_p=top_p, tuning=tuning)
+                ref = oracle_step(stored, codes, V, temp=temp, top_k=kk, top_p=top_p)
+                print("   ", compare_step(gpu, ref, V, label, trunc=True, codes=codes), flush=True)
+
+
 def test_step_three_pass_kernel():
     # the plain three-pass kernel, which no shape needs any more, forced by its knob
     _check(1001, 24, "bf16", seed=41, tuning={"step_shape": 9})
