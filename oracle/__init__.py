@@ -126,9 +126,9 @@ def step(logits, codes, temp=1.0, top_k=0, top_p=1.0, finished=None,
     """One decode step for every row.  Returns a dict of per-row arrays.
 
     With band > 0 and the nucleus on, rows whose running mass passes within `band` of top_p at a group end
-    also get the step under every other admissible closing of the nucleus: out["alt"] is a list of
+    also get the step under every other admissible closing of the nucleus: out["alt"] yields
     (shift, row indices, dict of arrays for those rows), one entry per shift != 0 that some row admits
-    (the C routine is simply called again for those rows with that shift).
+    (the C routine is simply called again for those rows with that shift, when the entry is asked for).
     """
     logits, dt = _stored(logits)
     if logits.ndim == 1:
@@ -142,21 +142,48 @@ def step(logits, codes, temp=1.0, top_k=0, top_p=1.0, finished=None,
     out = _step_call(logits, dt, ld, V, codes, temp, top_k, top_p, fin, eos_id, rid, nthreads, nuc_shift, band)
     call = dict(logits=logits, V=V, temp=temp, top_k=top_k, top_p=top_p, nthreads=nthreads)
     out["_call"] = dict(call, row_ids=rid, finished=fin, nuc_shift=nuc_shift)
-    out["alt"] = []
+    out["alt"] = _Alternatives(None, None, None)
     if band > 0.0 and 0.0 < top_p < 1.0 and nuc_shift == 0:
-        lo, hi = out["nuc_alt"][:, 0], out["nuc_alt"][:, 1]
         src = np.arange(rows, dtype=np.int64) if rid is None else rid
-        for shift in list(range(-int(lo.max(initial=0)), 0)) + list(range(1, int(hi.max(initial=0)) + 1)):
-            idx = np.nonzero((lo >= -shift) if shift < 0 else (hi >= shift))[0]
-            if idx.size == 0:
-                continue
+
+        def under(shift, idx):
             sub = _step_call(logits, dt, ld, V, np.ascontiguousarray(codes[idx]), temp, top_k, top_p,
                              None if fin is None else np.ascontiguousarray(fin[idx]), eos_id,
                              np.ascontiguousarray(src[idx]), nthreads, shift, band)
             sub["_call"] = dict(call, row_ids=np.ascontiguousarray(src[idx]),
                                 finished=None if fin is None else np.ascontiguousarray(fin[idx]), nuc_shift=shift)
-            out["alt"].append((shift, idx, sub))
+            return sub
+        out["alt"] = _Alternatives(under, out["nuc_alt"][:, 0].copy(), out["nuc_alt"][:, 1].copy())
     return out
+
+
+class _Alternatives:
+    """The step under the other admissible closings of the nucleus, computed when asked for: iterating gives
+    (shift, row indices, dict of arrays for those rows), nearest closings first (-1, +1, -2, +2, ...), one entry
+    per shift != 0 that some row admits.  among(rows) does the same for a subset of the rows (a boolean mask);
+    at most `limit` shifts a side (a nucleus whose top_p lies within the band of 1 admits thousands)."""
+
+    def __init__(self, under, lo, hi):
+        self.under, self.lo, self.hi = under, lo, hi
+
+    def among(self, mask=None, limit=None):
+        if self.under is None:
+            return
+        lo = self.lo if mask is None else np.where(mask, self.lo, 0)
+        hi = self.hi if mask is None else np.where(mask, self.hi, 0)
+        nlo, nhi = int(lo.max(initial=0)), int(hi.max(initial=0))
+        if limit is not None:
+            nlo, nhi = min(nlo, limit), min(nhi, limit)
+        for m in range(1, max(nlo, nhi) + 1):
+            for shift in (-m, m):
+                if (shift < 0 and m > nlo) or (shift > 0 and m > nhi):
+                    continue
+                idx = np.nonzero((lo >= m) if shift < 0 else (hi >= m))[0]
+                if idx.size:
+                    yield shift, idx, self.under(shift, idx)
+
+    def __iter__(self):
+        return self.among()
 
 
 def interval_in(step_result, rows, tokens):
