@@ -363,7 +363,7 @@ def main():
     ctx.profile(False)
     iv_us = iv_ms / max(iv_n, 1) * 1e3
     out["encode"] = {
-        "kernel": "interval_kernel (lookup of a given token instead of a search), inside as_encode",
+        "kernel": "interval_tile_kernel (the single-tile sampling kernel with a lookup of the given token in place of the search), inside as_encode",
         "avg_launch_us": iv_us, "launches": iv_n, "bound": "hbm",
         "achieved": active_rows_per_launch * bytes_per_row / (iv_us * 1e-6) / 1e9 if iv_n else None,
         "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -12,13 +12,16 @@ REL = 1e-5          # relative tolerance on a token's probability (fp32 weights,
 ABS_F = 2e-6        # absolute tolerance on a cumulative probability in [0, 1]
 
 
-def _interval_step(stored, tokens, V, temp=1.0, top_k=0, top_p=1.0, finished=None, eos_id=-1, lo0=None, w0=None):
+def _interval_step(stored, tokens, V, temp=1.0, top_k=0, top_p=1.0, finished=None, eos_id=-1, lo0=None, w0=None,
+                   tuning=None):
     import torch
     from paper_2210_15458_amd import binding as B
     from gpu_util import to_dev_logits
     logits = to_dev_logits(stored)
     R = tokens.shape[0]
     ctx = B.Ctx(R, V, logits.dtype)
+    for knob, value in (tuning or {}).items():
+        ctx.set_tuning(knob, value)
     lo = torch.from_numpy(np.zeros(R) if lo0 is None else lo0.copy()).cuda()
     w = torch.from_numpy(np.ones(R) if w0 is None else w0.copy()).cuda()
     fin_in = None if finished is None else torch.from_numpy(finished.astype(np.uint8)).cuda()
@@ -93,6 +96,51 @@ def test_interval_step_finished_rows_and_bad_tokens():
         else:
             assert abs(w[r] - p[r]) <= REL * p[r] and abs(lo[r] - f_lo[r]) <= ABS_F
             assert fout[r] == (1 if tokens[r] == eos else 0)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_interval_single_tile_kernel_edges(dtype):
+    """Rows of whole vectors that fit one tile take a kernel of their own (the single-tile sampling kernel with a
+    look-up in place of the search): tokens at the ends of elements, lanes, chunks, shares and of the row, tokens
+    outside the vocabulary, rows whose first chunk is tiny against what follows (sums beyond fp32: the block
+    falls back to the one-pass routine), masked rows, truncation, short and ragged rows; the one-pass kernel on
+    the same rows (the step-shape knob) must agree."""
+    import oracle
+    V = 32128 if dtype == "bf16" else 16000
+    epv = 8 if dtype == "bf16" else 4
+    rng = np.random.default_rng(491)
+    places = [0, 1, epv - 1, epv, 64 * epv - 1, 64 * epv, 1024 * epv - 1, 1024 * epv, 2048 * epv + 3, V - epv - 1, V - epv,
+              V - 1]
+    R = len(places) + 6
+    x = rng.normal(0.0, 3.0, (R, V)).astype(np.float32)
+    tokens = np.array(places + [5, 700, V // 2, -1, V, V + 100], dtype=np.int32)
+    x[len(places), :600] = -80.0; x[len(places), 700] = 80.0             # a first chunk that says little
+    x[len(places) + 1, :] = -60.0; x[len(places) + 1, 700] = 70.0         # the token is the far outlier itself
+    x[len(places) + 2, 1::2] = -np.inf
+    stored = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    for temp, top_k, top_p in [(1.0, 0, 1.0), (0.5, 0, 1.0), (1.0, 40, 1.0), (1.0, 0, 0.9), (0.05, 0, 1.0)]:
+        ok_tok = np.clip(tokens, 0, V - 1)
+        f_lo, p = oracle.token_interval(stored, ok_tok, temp=temp, top_k=top_k, top_p=top_p, V=V, nthreads=8)
+        res = {}
+        for shape in (0, 6):
+            lo, w, _ = _interval_step(stored, tokens, V, temp=temp, top_k=top_k, top_p=top_p, tuning={"step_shape": shape})
+            res[shape] = (lo, w)
+            for r in range(R):
+                if tokens[r] < 0 or tokens[r] >= V:
+                    assert w[r] == 0.0 and lo[r] == (0.0 if tokens[r] < 0 else 1.0), (temp, top_k, top_p, shape, r, lo[r], w[r])
+                else:
+                    # (weights are fp32 against the row's reference: probabilities below 2^-126 come out as 0)
+                    assert abs(w[r] - p[r]) <= REL * p[r] + 1e-36, (temp, top_k, top_p, shape, r, w[r], p[r])
+                    assert abs(lo[r] - f_lo[r]) <= ABS_F, (temp, top_k, top_p, shape, r, lo[r], f_lo[r])
+        # (the one-pass kernel, with a reference per thread, keeps probabilities below 2^-126 that the other loses)
+        assert np.allclose(res[0][1], res[6][1], rtol=2e-5, atol=1e-36) and np.allclose(res[0][0], res[6][0], rtol=0, atol=2e-6)
+    for Vs in (epv, 64 * epv, 65 * epv, 1024 * epv, 1025 * epv, 4096 * epv - epv, 4096 * epv):
+        st = synth.gaussian_logits(7, Vs, sigma=3.0, seed=Vs, dtype=dtype)
+        tk = rng.integers(0, Vs, 7).astype(np.int32)
+        tk[0], tk[1] = 0, Vs - 1
+        f_lo, p = oracle.token_interval(st, tk, temp=0.8, V=Vs, nthreads=8)
+        lo, w, _ = _interval_step(st, tk, Vs, temp=0.8)
+        assert np.all(np.abs(w - p) <= REL * p) and np.all(np.abs(lo - f_lo) <= ABS_F), Vs
 
 
 def _model(V, d, dtype, seed=0):
