@@ -1591,23 +1591,24 @@ __global__ __launch_bounds__(kThreads, 4) void topk_tile_kernel(StepArgs a, int3
 // equal logits is a count times one weight: the kernel counts, it does not add weights per logit.
 //   * while the row lands (loads and the look at the finished flag as in the single-tile sampling kernel) every
 //     logit goes into a table of counters in LDS, one per stored value in a window of kNucBins values that ends
-//     kNucMargin values (three factors of two) above the largest logit of the row's first chunks; values of the
-//     other sign or below the window go to a counter per lane that nobody reads.  Alongside, the sums of all
-//     weights per chunk, against one integer reference per wave, as in the sampling kernel (for the total).
+//     kNucMargin values (six factors of two: a confident row's one large logit is still inside) above the
+//     largest logit of the row's first chunks; values of the other sign or below the window go to a counter per
+//     lane that nobody reads.  Alongside, the sums of all weights per chunk, against one integer reference per
+//     wave, as in the sampling kernel (for the total).
 //   * after the barrier: 8 counters per thread become masses (count x weight of that value), a scan over the
 //     block finds the first value, from the top, at which the running mass reaches top_p of the total: the keep
 //     threshold; the group of equal logits that closes the nucleus stays whole (its counter is one group).
 //   * the counters give way to a table of weights, one per kept value: the chunk sums of the kept logits are
 //     look-ups and additions, and the search for the code's bucket over them is the sampling kernel's.
 // The row stays in registers throughout.  A logit above the window, a nucleus that does not close inside it (it
-// would have to reach down by a factor of 2^13 or across zero), sums beyond fp32: the block takes the general
+// would have to reach down by a factor of 2^10 below the first chunks' largest logit, or across zero), sums beyond fp32: the block takes the general
 // selection and the plain three-pass step instead.
 constexpr int kNucBins = 2048;
 #ifndef AS_NUC_AHEAD
 #define AS_NUC_AHEAD 4
 #endif
 constexpr int kNucAhead = AS_NUC_AHEAD;  // groups of four loads requested ahead of the group being counted
-constexpr int kNucMargin = 384;
+constexpr int kNucMargin = 768;
 
 struct TileNucleus {
     __attribute__((aligned(16))) uint32_t hist[kNucBins + 64];

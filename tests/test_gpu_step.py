@@ -323,7 +323,8 @@ def test_step_nucleus_single_tile_kernel_edges():
     V, R = 32128, 16
     rng = np.random.default_rng(291)
     x = rng.normal(0.0, 3.0, (R, V)).astype(np.float32)
-    x[0, 20000] = 200.0                              # far above the window's top
+    x[0, 20000] = 3.0e4                              # far above the window's top
+    x[14, 9000] = 150.0                              # a confident row: one logit far above the rest, inside the window
     x[1, :] = -np.abs(x[1, :]) - 0.25                # negative logits only
     x[2, :512] = -np.abs(x[2, :512]) - 1.0           # the first chunk of the first wave negative, the rest mixed
     for w in range(4):                                # every wave's first chunk negative, positive logits later
