@@ -54,21 +54,22 @@ def up(a):
     return torch.from_numpy(a).cuda()
 
 
-def sampling_kernel_name(V, ldt, top_k, top_p):
+def sampling_kernel_name(V, ldt, top_k, top_p, temp=1.0):
     """Which kernel finishes the sampling step for this shape (the choice the library makes)."""
     has_k, has_p = 0 < top_k < V, 0.0 < top_p < 1.0
     tile = V <= (32768 if ldt == "bf16" else 16384) and V % (8 if ldt == "bf16" else 4) == 0
+    first_chunk_reference_ok = 1.4426950408889634 / temp <= 4.0      # (the library's kTileMaxScale)
     if tile and ldt == "bf16" and has_k and top_k <= 48:
         return ("topk_tile_kernel (top-k%s and the sampling step in one launch, row resident in registers), "
                 "as launched inside as_decode" % (" + nucleus" if has_p else ""))
-    if tile and ldt == "bf16" and has_p and not has_k:
+    if tile and ldt == "bf16" and has_p and not has_k and first_chunk_reference_ok:
         return ("nucleus_tile_kernel (nucleus and the sampling step in one launch, logits counted by stored value), "
                 "as launched inside as_decode")
     if V <= 32768 and has_k and top_k <= 128:
         return "threshold_resident_kernel with the sampling step fused (top-k, candidates ranked in LDS), as launched inside as_decode"
     if has_k or has_p:
         return "threshold kernel, then the sampling-step kernel, as launched inside as_decode"
-    if tile:
+    if tile and first_chunk_reference_ok:
         return "step_tile_kernel (fused sampling step, one-tile rows), as launched inside as_decode"
     return "step_kernel (fused sampling step), as launched inside as_decode"
 
@@ -124,7 +125,7 @@ def compact_leg(cfg_id, top_k, top_p, steps, warmup):
                     f"temp={temp} top_k={top_k} top_p={top_p} eos={eos}",
         "value": R * T * steps / (t1 - t0), "unit": "code-steps/s", "decodes_timed": steps,
         "ms_per_decode": (t1 - t0) / steps * 1e3,
-        "sampling": {"kernel": sampling_kernel_name(V, "bf16", top_k, top_p), "bound": "hbm",
+        "sampling": {"kernel": sampling_kernel_name(V, "bf16", top_k, top_p, temp), "bound": "hbm",
                      "avg_launch_us": samp_us, "spread": spread(step_samples), "achieved": ach, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "bytes_per_code_step": bytes_per_row,
                      "active_rows_per_launch": act},
@@ -295,7 +296,7 @@ def main():
                    "value_over_a_longer_region": {"steps": long_steps, "value": R * T * long_steps / (t5 - t4),
                                                   "ms_per_step": (t5 - t4) / long_steps * 1e3}},
         "roofline": {
-            "kernel": sampling_kernel_name(V, ldt, top_k, top_p),
+            "kernel": sampling_kernel_name(V, ldt, top_k, top_p, temp),
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
             "avg_launch_us": step_avg_us, "launches": step_n, "untimed_launches": step_drop,

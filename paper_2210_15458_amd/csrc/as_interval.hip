@@ -358,7 +358,7 @@ as_status launch_interval(as_ctx *ctx, const IntervalArgs &a)
     const int epv = (int)(16 / esz);
     const bool tile = a.V % epv == 0 && a.V / epv <= kTileWaves * kTileIters * 64 &&
                       reinterpret_cast<uintptr_t>(a.logits) % 16 == 0 && (a.ld * (int64_t)esz) % 16 == 0 &&
-                      ctx->step_shape == 0;
+                      ctx->step_shape == 0 && a.k <= kTileMaxScale;
     if (tile) {
         if (a.dtype == AS_BF16) {
             if (a.thr) launch(ctx, kKernelInterval, interval_tile_kernel<AS_BF16, true>, grid, block, 0, a);

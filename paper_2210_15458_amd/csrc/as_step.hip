@@ -584,7 +584,7 @@ as_status launch_shape(as_ctx *ctx, const StepArgs &a)
     const int ntiles = (int)((nvec + tile - 1) / tile);
     const size_t lds = ((size_t)NW * ITERS * 64 + (size_t)ntiles * NW * 2) * sizeof(float);
     if (lds > 60 * 1024) return fail(ctx, AS_ERR_UNSUPPORTED, "vocabulary too large for the share table");
-    if (whole && ntiles == 1 && NW == 4 && ITERS == 16 && ctx->step_shape == 0)
+    if (whole && ntiles == 1 && NW == 4 && ITERS == 16 && ctx->step_shape == 0 && a.k <= kTileMaxScale)
         launch(ctx, kKernelStep, step_tile_kernel<DT, HAS_THR>, dim3((unsigned)a.rows), dim3(256), 0, a);
     else if (!whole)
         launch(ctx, kKernelStep, step_kernel<DT, NW, ITERS, OCC, HAS_THR, true>, dim3((unsigned)a.rows), dim3(NW * 64),

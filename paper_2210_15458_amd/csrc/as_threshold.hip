@@ -1927,7 +1927,7 @@ bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p
         if (e != hipSuccess) *st = hip_fail(ctx, e, "top-k step launch");
         return true;
     }
-    if (nucleus_only && ctx->V % 8 == 0 && ctx->thr_path != 2) {
+    if (nucleus_only && ctx->V % 8 == 0 && ctx->thr_path != 2 && a.k <= kTileMaxScale) {
         launch(ctx, kKernelStep, nucleus_tile_kernel, grid, block, 0, a, top_p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) *st = hip_fail(ctx, e, "nucleus step launch");

@@ -111,6 +111,11 @@ __device__ __forceinline__ void wave_sum4_in_lane63(float &a, float &b, float &c
 // ---------------------------------------------------------------------------
 // a row of whole, aligned vectors in one tile
 constexpr int kTileWaves = 4, kTileIters = 16, kTileGroup = 4;
+// The kernels that take a wave's reference from its share's first chunk lose a row to their slow path when a
+// logit lies more than 127/k above that chunk's largest (weights beyond fp32).  The host keeps them for
+// k = log2(e)/temp up to this: a logit 30 above the first chunk's largest still fits.  Lower temperatures take
+// the kernels that follow the running maximum.
+constexpr float kTileMaxScale = 4.f;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct TileSums {
