@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kThreads) void interval_kernel(IntervalArgs a)
 // barrier; then every wave scans the 64 chunk sums (fp64) for the total and the mass before the token's chunk,
 // and the wave that holds the token's chunk adds the lanes before it and the elements before it.  Sums that
 // leave fp32 against a first-chunk reference send the block to the one-pass routine above.
-template <int DT, bool HAS_THR>
+template <int DT, bool HAS_THR, bool NT>
 __global__ __launch_bounds__(kThreads, 4) void interval_tile_kernel(IntervalArgs a)
 {
     using T = typename Elem<DT>::T;
@@ -246,11 +246,22 @@ __global__ __launch_bounds__(kThreads, 4) void interval_tile_kernel(IntervalArgs
     const uint32_t off0 = (uint32_t)lane * 16u;
     const uint32_t off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
     auto request_group = [&](int g) __attribute__((always_inline)) {
+        // (ordinary loads where the tensor fits the caches, the non-temporal hint where it is streamed from HBM;
+        // each load behind the two vector instructions of its own offset either way)
+        if constexpr (NT) {
 #pragma unroll
-        for (int jj = 0; jj < G; ++jj) {
-            uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
-            off = off < off_last ? off : off_last;
-            raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+            for (int jj = 0; jj < G; ++jj) {
+                uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                off = off < off_last ? off : off_last;
+                raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+            }
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                off = off < off_last ? off : off_last;
+                raw[g * G + jj] = *reinterpret_cast<const u32x4 *>(base + off);
+            }
         }
     };
     if (live) request_group(0);
@@ -350,23 +361,28 @@ __global__ void interval_init_kernel(int32_t B, int32_t N, const int32_t *prompt
 
 }  // namespace
 
-as_status launch_interval(as_ctx *ctx, const IntervalArgs &a)
+as_status launch_interval(as_ctx *ctx, const IntervalArgs &args)
 {
-    if (a.rows == 0) return AS_OK;
+    if (args.rows == 0) return AS_OK;
+    const IntervalArgs &a = args;
     const dim3 grid((unsigned)a.rows), block(kThreads);
     const size_t esz = a.dtype == AS_BF16 ? 2 : 4;
+    const bool nt = stream_rows(a.rows, a.ld, esz);
     const int epv = (int)(16 / esz);
     const bool tile = a.V % epv == 0 && a.V / epv <= kTileWaves * kTileIters * 64 &&
                       reinterpret_cast<uintptr_t>(a.logits) % 16 == 0 && (a.ld * (int64_t)esz) % 16 == 0 &&
                       ctx->step_shape == 0 && a.k <= kTileMaxScale;
     if (tile) {
-        if (a.dtype == AS_BF16) {
-            if (a.thr) launch(ctx, kKernelInterval, interval_tile_kernel<AS_BF16, true>, grid, block, 0, a);
-            else launch(ctx, kKernelInterval, interval_tile_kernel<AS_BF16, false>, grid, block, 0, a);
-        } else {
-            if (a.thr) launch(ctx, kKernelInterval, interval_tile_kernel<AS_F32, true>, grid, block, 0, a);
-            else launch(ctx, kKernelInterval, interval_tile_kernel<AS_F32, false>, grid, block, 0, a);
-        }
+#define AS_INTERVAL_TILE(DT_)                                                                                   \
+    do {                                                                                                        \
+        if (a.thr && nt) launch(ctx, kKernelInterval, interval_tile_kernel<DT_, true, true>, grid, block, 0, a);   \
+        else if (a.thr) launch(ctx, kKernelInterval, interval_tile_kernel<DT_, true, false>, grid, block, 0, a);   \
+        else if (nt) launch(ctx, kKernelInterval, interval_tile_kernel<DT_, false, true>, grid, block, 0, a);      \
+        else launch(ctx, kKernelInterval, interval_tile_kernel<DT_, false, false>, grid, block, 0, a);             \
+    } while (0)
+        if (a.dtype == AS_BF16) AS_INTERVAL_TILE(AS_BF16);
+        else AS_INTERVAL_TILE(AS_F32);
+#undef AS_INTERVAL_TILE
     } else if (a.dtype == AS_BF16) {
         launch(ctx, kKernelInterval, interval_kernel<uint16_t>, grid, block, 0, a);
     } else {

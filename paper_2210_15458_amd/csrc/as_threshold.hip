@@ -1288,7 +1288,7 @@ struct TileTopK {
     __attribute__((aligned(16))) double cw[kTileCand];
 };
 
-template <bool HAS_P>
+template <bool HAS_P, bool NT>
 __global__ __launch_bounds__(kThreads, 4) void topk_tile_kernel(StepArgs a, int32_t top_k, float top_p)
 {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -1332,11 +1332,22 @@ __global__ __launch_bounds__(kThreads, 4) void topk_tile_kernel(StepArgs a, int3
     const uint32_t off0 = (uint32_t)lane * 16u;
     const uint32_t off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
     auto request_group = [&](int g) __attribute__((always_inline)) {
+        // (ordinary loads where the tensor fits the caches, the non-temporal hint where it is streamed from HBM;
+        // each load behind the two vector instructions of its own offset either way)
+        if constexpr (NT) {
 #pragma unroll
-        for (int jj = 0; jj < G; ++jj) {
-            uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
-            off = off < off_last ? off : off_last;
-            raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+            for (int jj = 0; jj < G; ++jj) {
+                uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                off = off < off_last ? off : off_last;
+                raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+            }
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                off = off < off_last ? off : off_last;
+                raw[g * G + jj] = *reinterpret_cast<const u32x4 *>(base + off);
+            }
         }
     };
     if (live) request_group(0);
@@ -1629,6 +1640,7 @@ __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b)
     return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, a) - __builtin_bit_cast(u16x2, b)));
 }
 
+template <bool NT>
 __global__ __launch_bounds__(kThreads, 4) void nucleus_tile_kernel(StepArgs a, float top_p)
 {
     constexpr int DT = AS_BF16;
@@ -1669,11 +1681,22 @@ __global__ __launch_bounds__(kThreads, 4) void nucleus_tile_kernel(StepArgs a, f
     const uint32_t off0 = (uint32_t)lane * 16u;
     const uint32_t off_last = mych > 0 ? off0 + (uint32_t)(mych - 1) * 1024u : 0u;
     auto request_group = [&](int g) __attribute__((always_inline)) {
+        // (ordinary loads where the tensor fits the caches, the non-temporal hint where it is streamed from HBM;
+        // each load behind the two vector instructions of its own offset either way)
+        if constexpr (NT) {
 #pragma unroll
-        for (int jj = 0; jj < G; ++jj) {
-            uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
-            off = off < off_last ? off : off_last;
-            raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+            for (int jj = 0; jj < G; ++jj) {
+                uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                off = off < off_last ? off : off_last;
+                raw[g * G + jj] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off));
+            }
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                uint32_t off = off0 + (uint32_t)(g * G + jj) * 1024u;
+                off = off < off_last ? off : off_last;
+                raw[g * G + jj] = *reinterpret_cast<const u32x4 *>(base + off);
+            }
         }
     };
     // the counters start at zero (before anything is loaded: the registers of the row are not free later)
@@ -1909,9 +1932,11 @@ void launch_resident(as_ctx *ctx, const void *logits, int64_t rows, int64_t ld, 
 
 // top-k (optionally followed by the nucleus), or the nucleus alone on bf16 rows, and the sampling step in one
 // launch; false if the shape does not qualify (then the caller runs the threshold kernel and the step kernel one after the other)
-bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p, as_status *st)
+bool launch_topk_step(as_ctx *ctx, const StepArgs &args, int32_t top_k, float top_p, as_status *st)
 {
     const size_t esz = ctx->dtype == AS_BF16 ? 2 : 4;
+    const StepArgs &a = args;
+    const bool nt = stream_rows(a.rows, a.ld, esz);
     const bool has_k = top_k > 0 && top_k < ctx->V, has_p = top_p > 0.f && top_p < 1.f;
     const bool nucleus_only = !has_k && has_p && ctx->dtype == AS_BF16;
     if ((ctx->thr_path != 0 && ctx->thr_path != 2) || !(has_k || nucleus_only) || top_k > kThreads / 2 || ctx->V > 32768 ||
@@ -1921,14 +1946,17 @@ bool launch_topk_step(as_ctx *ctx, const StepArgs &a, int32_t top_k, float top_p
     if (a.rows == 0) return true;
     const dim3 grid((unsigned)a.rows), block(kThreads);
     if (has_k && top_k <= kTileTopK && ctx->dtype == AS_BF16 && ctx->V % 8 == 0 && ctx->thr_path != 2) {
-        if (has_p) launch(ctx, kKernelStep, topk_tile_kernel<true>, grid, block, 0, a, top_k, top_p);
-        else launch(ctx, kKernelStep, topk_tile_kernel<false>, grid, block, 0, a, top_k, top_p);
+        if (has_p && nt) launch(ctx, kKernelStep, topk_tile_kernel<true, true>, grid, block, 0, a, top_k, top_p);
+        else if (has_p) launch(ctx, kKernelStep, topk_tile_kernel<true, false>, grid, block, 0, a, top_k, top_p);
+        else if (nt) launch(ctx, kKernelStep, topk_tile_kernel<false, true>, grid, block, 0, a, top_k, top_p);
+        else launch(ctx, kKernelStep, topk_tile_kernel<false, false>, grid, block, 0, a, top_k, top_p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) *st = hip_fail(ctx, e, "top-k step launch");
         return true;
     }
     if (nucleus_only && ctx->V % 8 == 0 && ctx->thr_path != 2 && a.k <= kTileMaxScale) {
-        launch(ctx, kKernelStep, nucleus_tile_kernel, grid, block, 0, a, top_p);
+        if (nt) launch(ctx, kKernelStep, nucleus_tile_kernel<true>, grid, block, 0, a, top_p);
+        else launch(ctx, kKernelStep, nucleus_tile_kernel<false>, grid, block, 0, a, top_p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) *st = hip_fail(ctx, e, "nucleus step launch");
         return true;
